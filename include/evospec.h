@@ -1,0 +1,145 @@
+/*
+ * evospec.h -- C ABI of the MI355X (gfx950) active-vocabulary LM head.
+ *
+ * The operation is the draft model's output projection of the EvoSpec paper,
+ * Eq. 1  p = Softmax(h W_LM^T), evaluated only on the active vocabulary
+ * V_t = V_static u V_dyn (Eq. 3; Algorithm 1, "construct active subspace" and
+ * "draft restricted to V_t"), followed by the top-k that expands the draft tree
+ * (EAGLE-2 search depth 6, 60-token budget; "Metrics and implementation details").
+ *
+ * Conventions for every call
+ *   - extern "C", returns an evospec_status; never throws.
+ *   - Pointers marked `dev` are device (HBM) addresses, `host` are host addresses.
+ *     The caller owns every buffer; the library allocates no device memory and never
+ *     synchronises (except evospec_validate_ids, a debug aid).
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and is ordered with other work on that stream.
+ *   - bf16 matrices are row-major with contiguous rows (leading dimension == d),
+ *     base pointers 16-byte aligned, d a multiple of 8 (128-bit loads).
+ *   - Arguments are validated on the host before the first HIP call; on an error
+ *     nothing is enqueued.
+ *   - M == 0 or n == 0 is a legal no-op (an update event may admit no token:
+ *     App. "Additional safeguards").
+ */
+#ifndef EVOSPEC_H
+#define EVOSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EVOSPEC_VERSION 100
+#define EVOSPEC_K_MAX 64        /* largest k of the fused top-k                         */
+#define EVOSPEC_M_TILE 64       /* draft rows handled by one pass over W_act            */
+
+typedef enum evospec_status {
+    EVOSPEC_OK = 0,
+    EVOSPEC_NULL_POINTER = 1,       /* a required pointer is NULL                         */
+    EVOSPEC_BAD_SHAPE = 2,          /* negative size, V_act <= 0, d <= 0, d % 8 != 0, ... */
+    EVOSPEC_BAD_K = 3,              /* k < 1, k > EVOSPEC_K_MAX or k > active-set size    */
+    EVOSPEC_MISALIGNED = 4,         /* a matrix / workspace pointer is not 16-B aligned   */
+    EVOSPEC_WORKSPACE_TOO_SMALL = 5,
+    EVOSPEC_BAD_SEGMENTS = 6,       /* row_off not monotone, row_off[0]!=0, row_off[S]!=M */
+    EVOSPEC_INVALID_IDS = 7,        /* evospec_validate_ids only                          */
+    EVOSPEC_HIP_ERROR = 8           /* a launch failed; text via evospec_last_hip_error() */
+} evospec_status;
+
+int evospec_version(void);
+/* Static, never freed. */
+const char *evospec_status_string(int status);
+/* Text of the last HIP error seen by this thread's calls ("" if none). Static storage. */
+const char *evospec_last_hip_error(void);
+
+/*
+ * Bytes of device scratch that evospec_active_lmhead_topk needs for these shapes
+ * (host only, no HIP call).  The scratch holds, per slab of W_act rows and per draft
+ * row, the slab's running max, sum of exponentials and k best (logit, id) pairs.
+ */
+int evospec_workspace_bytes(int M, int V_act, int d, int k, size_t *out_bytes /*host*/);
+/* Same for the segmented call. */
+int evospec_workspace_bytes_segmented(int M, int V_core, int V_arc, int S, int d, int k,
+                                      size_t *out_bytes /*host*/);
+
+/*
+ * Insert rows into the compact active matrix (Eq. 3 builds V_t as a union; App.
+ * "HNSW semantic retrieval": retrieved ids are inserted into the active draft
+ * vocabulary; App. "ARC-based dynamic vocabulary maintenance" decides which slot).
+ *   for i in [0, n):  W_act[slot_i, :] = W_lm[src_ids[i], :]   (bit-exact copy)
+ *                     act_ids[slot_i]  = src_ids[i]
+ *   slots == NULL means slot_i = i (full rebuild, then n <= V_act is required).
+ * W_lm   dev bf16 [V, d]          src_ids dev int32 [n]     slots dev int32 [n] or NULL
+ * W_act  dev bf16 [V_act, d]      act_ids dev int32 [V_act]
+ * Preconditions not checked here (see evospec_validate_ids): 0 <= src_ids[i] < V,
+ * 0 <= slots[i] < V_act, slots distinct within a call, W_act not overlapping W_lm.
+ * Entries with an out-of-range id or slot are skipped by the kernel (memory safe).
+ * Stream ordered: a later evospec_active_lmhead_topk on the same stream sees the update;
+ * if the update is not enqueued in time the old W_act stays valid ("Retrieval latency
+ * and asynchronous execution": a late result merges into a subsequent launch).
+ */
+int evospec_active_gather(const void *W_lm, int V, int d,
+                          const int32_t *src_ids, const int32_t *slots, int n,
+                          void *W_act, int32_t *act_ids, int V_act, void *stream);
+
+/*
+ * The restricted head (Eq. 1 on V_t; Algorithm 1 draft phase).  For each draft row m:
+ *   z[m, i]    = sum_j h[m, j] * W_act[i, j]              i in [0, V_act)   (bf16 x bf16, fp32 accumulate)
+ *   out_logz[m]= log sum_i exp(z[m, i])                   (normaliser over the active set only)
+ *   out_vals[m, 0..k) = the k largest z[m, i], descending; equal logits ordered by smaller
+ *                       full-vocabulary id first
+ *   out_ids[m, 0..k)  = ids[i] of those entries (ids == NULL: the slot index i itself)
+ * log-probability of a returned entry = out_vals - out_logz.  Logits are never written to HBM.
+ * h dev bf16 [M, d]   W_act dev bf16 [V_act, d]   ids dev int32 [V_act] or NULL
+ * out_vals dev f32 [M, k]   out_ids dev int32 [M, k]   out_logz dev f32 [M]
+ * workspace dev, 16-B aligned, at least evospec_workspace_bytes(...) bytes; contents are
+ * scratch.  Two calls that share a workspace must be ordered (same stream).
+ * Any M >= 0; rows are processed in passes of EVOSPEC_M_TILE.  ids must be unique
+ * (Eq. 3 is a set union); duplicates are memory safe but count twice in the normaliser.
+ */
+int evospec_active_lmhead_topk(const void *h, int M, int d,
+                               const void *W_act, const int32_t *ids, int V_act, int k,
+                               float *out_vals, int32_t *out_ids, float *out_logz,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The two halves of evospec_active_lmhead_topk, exposed so that a caller (or a profiler)
+ * can time or overlap them: _partials streams W_act once and leaves per-slab partial
+ * results in the workspace; _merge reduces them into the outputs.  Calling them back to
+ * back on one stream with the same arguments is exactly evospec_active_lmhead_topk.
+ */
+int evospec_active_lmhead_partials(const void *h, int M, int d,
+                                   const void *W_act, const int32_t *ids, int V_act, int k,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+int evospec_active_lmhead_merge(int M, int V_act, int d, int k,
+                                float *out_vals, int32_t *out_ids, float *out_logz,
+                                const void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Batched serving variant (not in the paper; several requests share the static core and
+ * each carries its own dynamic buffer).  Rows [row_off[s], row_off[s+1]) of h belong to
+ * sequence s and see the active set  core u arc[s]  (caller promises arc[s] is disjoint
+ * from the core).  Outputs as above, normaliser over core u arc[s].
+ * W_core dev bf16 [V_core, d]  ids_core dev int32 [V_core] or NULL (identity)
+ * W_arc  dev bf16 [S, V_arc, d] ids_arc dev int32 [S, V_arc]
+ * row_off HOST int32 [S+1], row_off[0] == 0, non-decreasing, row_off[S] == M.
+ */
+int evospec_active_lmhead_topk_segmented(const void *h, int M, int d,
+        const void *W_core, const int32_t *ids_core, int V_core,
+        const void *W_arc, const int32_t *ids_arc, int V_arc,
+        const int32_t *row_off, int S, int k,
+        float *out_vals, int32_t *out_ids, float *out_logz,
+        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Debug aid: checks 0 <= ids[i] < V and that no id occurs twice (Eq. 3 is a set).
+ * Launches one check kernel and waits for it (the only call that synchronises).
+ * Returns EVOSPEC_OK or EVOSPEC_INVALID_IDS.  ids dev int32 [n].
+ */
+int evospec_validate_ids(const int32_t *ids, int n, int V, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EVOSPEC_H */

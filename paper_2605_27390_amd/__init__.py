@@ -1,0 +1,24 @@
+"""MI355X-native active-vocabulary LM head (EvoSpec, Eq. 1 restricted to V_t) -- Python binding.
+
+The package is a thin ctypes layer over `libevospec.so` (hand-written HIP for gfx950 behind the
+C ABI of `include/evospec.h`).  It has no CPU fallback: importing it without the built library
+raises.  Build the library with `python -m paper_2605_27390_amd.build` or `__graft_entry__.build()`.
+"""
+from .binding import (  # noqa: F401
+    EvospecError,
+    K_MAX,
+    M_TILE,
+    STATUS,
+    lib,
+    lib_path,
+    version,
+    status_string,
+    workspace_bytes,
+    workspace_bytes_segmented,
+    active_gather,
+    active_lmhead_topk,
+    active_lmhead_partials,
+    active_lmhead_merge,
+    active_lmhead_topk_segmented,
+    validate_ids,
+)

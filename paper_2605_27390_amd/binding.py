@@ -1,0 +1,225 @@
+"""ctypes binding of the C ABI in include/evospec.h: argument marshalling only.
+
+Tensors are torch tensors on the GPU (bf16 matrices, int32 ids, fp32/int32 outputs); the
+binding passes their device pointers and torch's current HIP stream.  Every step of the path
+runs inside the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libevospec.so")
+
+K_MAX = 64
+M_TILE = 64
+STATUS = {
+    0: "OK", 1: "NULL_POINTER", 2: "BAD_SHAPE", 3: "BAD_K", 4: "MISALIGNED",
+    5: "WORKSPACE_TOO_SMALL", 6: "BAD_SEGMENTS", 7: "INVALID_IDS", 8: "HIP_ERROR",
+}
+
+
+class EvospecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.evospec_status_string(status).decode()
+        if status == 8:
+            msg += ": " + lib.evospec_last_hip_error().decode()
+        super().__init__(f"{where}: {STATUS.get(status, status)} ({msg})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2605_27390_amd.build` "
+            "(hipcc, gfx950).  There is no CPU fallback.")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.evospec_version.restype = ci
+    L.evospec_status_string.restype = ctypes.c_char_p
+    L.evospec_status_string.argtypes = [ci]
+    L.evospec_last_hip_error.restype = ctypes.c_char_p
+    L.evospec_workspace_bytes.restype = ci
+    L.evospec_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
+    L.evospec_workspace_bytes_segmented.restype = ci
+    L.evospec_workspace_bytes_segmented.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(sz)]
+    L.evospec_active_gather.restype = ci
+    L.evospec_active_gather.argtypes = [vp, ci, ci, vp, vp, ci, vp, vp, ci, vp]
+    L.evospec_active_lmhead_topk.restype = ci
+    L.evospec_active_lmhead_topk.argtypes = [vp, ci, ci, vp, vp, ci, ci, vp, vp, vp, vp, sz, vp]
+    L.evospec_active_lmhead_partials.restype = ci
+    L.evospec_active_lmhead_partials.argtypes = [vp, ci, ci, vp, vp, ci, ci, vp, sz, vp]
+    L.evospec_active_lmhead_merge.restype = ci
+    L.evospec_active_lmhead_merge.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    L.evospec_active_lmhead_topk_segmented.restype = ci
+    L.evospec_active_lmhead_topk_segmented.argtypes = [vp, ci, ci, vp, vp, ci, vp, vp, ci,
+                                                       ctypes.POINTER(ctypes.c_int32), ci, ci,
+                                                       vp, vp, vp, vp, sz, vp]
+    L.evospec_validate_ids.restype = ci
+    L.evospec_validate_ids.argtypes = [vp, ci, ci, vp]
+    return L
+
+
+lib = _load()
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def version() -> int:
+    return int(lib.evospec_version())
+
+
+def status_string(status: int) -> str:
+    return lib.evospec_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise EvospecError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _expect(t, dtype, name, ndim=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU torch tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if ndim is not None and t.dim() != ndim:
+        raise ValueError(f"{name} must have {ndim} dims")
+
+
+def workspace_bytes(M: int, V_act: int, d: int, k: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib.evospec_workspace_bytes(M, V_act, d, k, ctypes.byref(out)), "evospec_workspace_bytes")
+    return int(out.value)
+
+
+def workspace_bytes_segmented(M: int, V_core: int, V_arc: int, S: int, d: int, k: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib.evospec_workspace_bytes_segmented(M, V_core, V_arc, S, d, k, ctypes.byref(out)),
+           "evospec_workspace_bytes_segmented")
+    return int(out.value)
+
+
+def active_gather(W_lm, src_ids, slots, W_act, act_ids) -> None:
+    """W_act[slot_i] = W_lm[src_ids[i]], act_ids[slot_i] = src_ids[i] (slots=None: slot_i = i)."""
+    import torch
+    _expect(W_lm, torch.bfloat16, "W_lm", 2)
+    _expect(W_act, torch.bfloat16, "W_act", 2)
+    _expect(src_ids, torch.int32, "src_ids", 1)
+    _expect(act_ids, torch.int32, "act_ids", 1)
+    if slots is not None:
+        _expect(slots, torch.int32, "slots", 1)
+        if slots.shape[0] != src_ids.shape[0]:
+            raise ValueError("slots and src_ids differ in length")
+    V, d = W_lm.shape
+    V_act = W_act.shape[0]
+    if W_act.shape[1] != d or act_ids.shape[0] != V_act:
+        raise ValueError("W_act / act_ids shapes do not match")
+    _check(lib.evospec_active_gather(_ptr(W_lm), V, d, _ptr(src_ids), _ptr(slots), src_ids.shape[0],
+                                     _ptr(W_act), _ptr(act_ids), V_act, _stream()), "evospec_active_gather")
+
+
+def _head_shapes(h, W_act, ids):
+    import torch
+    _expect(h, torch.bfloat16, "h", 2)
+    _expect(W_act, torch.bfloat16, "W_act", 2)
+    M, d = h.shape
+    V_act = W_act.shape[0]
+    if W_act.shape[1] != d:
+        raise ValueError("hidden sizes of h and W_act differ")
+    if ids is not None:
+        _expect(ids, torch.int32, "ids", 1)
+        if ids.shape[0] != V_act:
+            raise ValueError("ids length != V_act")
+    return M, d, V_act
+
+
+def _workspace(workspace, need, device):
+    import torch
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def active_lmhead_topk(h, W_act, ids, k, out_vals=None, out_ids=None, out_logz=None, workspace=None):
+    """Restricted head: returns (vals[M,k] f32, ids[M,k] i32, logz[M] f32)."""
+    import torch
+    M, d, V_act = _head_shapes(h, W_act, ids)
+    dev = h.device
+    out_vals = torch.empty((M, k), dtype=torch.float32, device=dev) if out_vals is None else out_vals
+    out_ids = torch.empty((M, k), dtype=torch.int32, device=dev) if out_ids is None else out_ids
+    out_logz = torch.empty((M,), dtype=torch.float32, device=dev) if out_logz is None else out_logz
+    if workspace is None:
+        workspace = _workspace(None, workspace_bytes(M, V_act, d, k), dev)
+    _check(lib.evospec_active_lmhead_topk(_ptr(h), M, d, _ptr(W_act), _ptr(ids), V_act, k,
+                                          _ptr(out_vals), _ptr(out_ids), _ptr(out_logz),
+                                          _ptr(workspace), workspace.numel(), _stream()),
+           "evospec_active_lmhead_topk")
+    return out_vals, out_ids, out_logz
+
+
+def active_lmhead_partials(h, W_act, ids, k, workspace) -> None:
+    M, d, V_act = _head_shapes(h, W_act, ids)
+    _check(lib.evospec_active_lmhead_partials(_ptr(h), M, d, _ptr(W_act), _ptr(ids), V_act, k,
+                                              _ptr(workspace), workspace.numel(), _stream()),
+           "evospec_active_lmhead_partials")
+
+
+def active_lmhead_merge(M, V_act, d, k, out_vals, out_ids, out_logz, workspace) -> None:
+    _check(lib.evospec_active_lmhead_merge(M, V_act, d, k, _ptr(out_vals), _ptr(out_ids), _ptr(out_logz),
+                                           _ptr(workspace), workspace.numel(), _stream()),
+           "evospec_active_lmhead_merge")
+
+
+def active_lmhead_topk_segmented(h, W_core, ids_core, W_arc, ids_arc, row_off, k, workspace=None):
+    """Batched variant: rows [row_off[s], row_off[s+1]) see core u arc[s]. row_off: host ints."""
+    import torch
+    _expect(h, torch.bfloat16, "h", 2)
+    _expect(W_core, torch.bfloat16, "W_core", 2)
+    _expect(W_arc, torch.bfloat16, "W_arc", 3)
+    _expect(ids_arc, torch.int32, "ids_arc", 2)
+    if ids_core is not None:
+        _expect(ids_core, torch.int32, "ids_core", 1)
+    M, d = h.shape
+    V_core = W_core.shape[0]
+    S, V_arc, d2 = W_arc.shape
+    if W_core.shape[1] != d or d2 != d or tuple(ids_arc.shape) != (S, V_arc):
+        raise ValueError("shape mismatch")
+    ro = (ctypes.c_int32 * (S + 1))(*[int(x) for x in row_off])
+    dev = h.device
+    out_vals = torch.empty((M, k), dtype=torch.float32, device=dev)
+    out_ids = torch.empty((M, k), dtype=torch.int32, device=dev)
+    out_logz = torch.empty((M,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(None, workspace_bytes_segmented(M, V_core, V_arc, S, d, k), dev)
+    _check(lib.evospec_active_lmhead_topk_segmented(
+        _ptr(h), M, d, _ptr(W_core), _ptr(ids_core), V_core, _ptr(W_arc), _ptr(ids_arc), V_arc,
+        ro, S, k, _ptr(out_vals), _ptr(out_ids), _ptr(out_logz), _ptr(workspace), workspace.numel(),
+        _stream()), "evospec_active_lmhead_topk_segmented")
+    return out_vals, out_ids, out_logz
+
+
+def validate_ids(ids, V: int) -> bool:
+    """True when every id is in [0, V) and no id repeats (synchronises)."""
+    import torch
+    _expect(ids, torch.int32, "ids", 1)
+    st = lib.evospec_validate_ids(_ptr(ids), ids.shape[0], V, _stream())
+    if st == 7:
+        return False
+    _check(st, "evospec_validate_ids")
+    return True

@@ -1,0 +1,260 @@
+// C ABI of the active-vocabulary LM head (declared in include/evospec.h): argument
+// validation on the host, launch planning, and the sequence of kernel launches.
+// Nothing here allocates device memory or waits for the GPU (evospec_validate_ids aside).
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "evospec.h"
+#include "launch.hpp"
+#include "plan.hpp"
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e) {
+    std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
+    return EVOSPEC_HIP_ERROR;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Compute units of the current device (cached per device id).
+int device_num_cu(int* out) {
+    static int cached[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev >= 0 && dev < 64 && cached[dev] > 0) { *out = cached[dev]; return EVOSPEC_OK; }
+    int n = 0;
+    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (n <= 0) n = 256;
+    if (dev >= 0 && dev < 64) cached[dev] = n;
+    *out = n;
+    return EVOSPEC_OK;
+}
+
+int check_head_args(const void* h, int M, int d, const void* W, int V_act, int k) {
+    if (M < 0 || d <= 0 || (d % 8) != 0 || V_act <= 0) return EVOSPEC_BAD_SHAPE;
+    if (k < 1 || k > EVOSPEC_K_MAX || k > V_act) return EVOSPEC_BAD_K;
+    if (M > 0 && (!h || !W)) return EVOSPEC_NULL_POINTER;
+    if (M > 0 && (!aligned16(h) || !aligned16(W))) return EVOSPEC_MISALIGNED;
+    return EVOSPEC_OK;
+}
+
+}  // namespace
+
+using namespace evospec;
+
+extern "C" {
+
+int evospec_version(void) { return EVOSPEC_VERSION; }
+
+const char* evospec_status_string(int status) {
+    switch (status) {
+        case EVOSPEC_OK: return "ok";
+        case EVOSPEC_NULL_POINTER: return "a required pointer is NULL";
+        case EVOSPEC_BAD_SHAPE: return "bad shape (negative size, V_act <= 0, d <= 0 or d not a multiple of 8)";
+        case EVOSPEC_BAD_K: return "k must satisfy 1 <= k <= min(EVOSPEC_K_MAX, active-set size)";
+        case EVOSPEC_MISALIGNED: return "matrix or workspace pointer is not 16-byte aligned";
+        case EVOSPEC_WORKSPACE_TOO_SMALL: return "workspace is smaller than evospec_workspace_bytes reports";
+        case EVOSPEC_BAD_SEGMENTS: return "row_off must start at 0, be non-decreasing and end at M";
+        case EVOSPEC_INVALID_IDS: return "ids out of range or not unique";
+        case EVOSPEC_HIP_ERROR: return "HIP error (see evospec_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+const char* evospec_last_hip_error(void) { return g_hip_error; }
+
+int evospec_workspace_bytes(int M, int V_act, int d, int k, size_t* out_bytes) {
+    if (!out_bytes) return EVOSPEC_NULL_POINTER;
+    if (M < 0 || d <= 0 || (d % 8) != 0 || V_act <= 0) return EVOSPEC_BAD_SHAPE;
+    if (k < 1 || k > EVOSPEC_K_MAX || k > V_act) return EVOSPEC_BAD_K;
+    *out_bytes = workspace_upper_bound(V_act, k);      // passes over M reuse the same scratch
+    return EVOSPEC_OK;
+}
+
+int evospec_workspace_bytes_segmented(int M, int V_core, int V_arc, int S, int d, int k, size_t* out_bytes) {
+    if (!out_bytes) return EVOSPEC_NULL_POINTER;
+    if (M < 0 || d <= 0 || (d % 8) != 0 || V_core < 0 || V_arc < 0 || V_core + V_arc <= 0 || S <= 0)
+        return EVOSPEC_BAD_SHAPE;
+    if (k < 1 || k > EVOSPEC_K_MAX || k > V_core + V_arc) return EVOSPEC_BAD_K;
+    // core partials are kept for every 64-row pass; the extension scratch is reused per chunk
+    const size_t passes = ((size_t)M + kMTile - 1) / kMTile;
+    size_t total = 0;
+    if (V_core > 0) total += passes * workspace_upper_bound(V_core, k);
+    if (V_arc > 0) total += workspace_upper_bound(V_arc, k);
+    *out_bytes = total > 0 ? total : 256;
+    return EVOSPEC_OK;
+}
+
+int evospec_active_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
+                          int n, void* W_act, int32_t* act_ids, int V_act, void* stream) {
+    if (V <= 0 || d <= 0 || (d % 8) != 0 || V_act <= 0 || n < 0) return EVOSPEC_BAD_SHAPE;
+    if (!slots && n > V_act) return EVOSPEC_BAD_SHAPE;
+    if (n == 0) return EVOSPEC_OK;
+    if (!W_lm || !src_ids || !W_act || !act_ids) return EVOSPEC_NULL_POINTER;
+    if (!aligned16(W_lm) || !aligned16(W_act)) return EVOSPEC_MISALIGNED;
+    hipError_t e = launch_gather(W_lm, V, d, src_ids, slots, n, W_act, act_ids, V_act,
+                                 static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
+}
+
+int evospec_active_lmhead_partials(const void* h, int M, int d, const void* W_act, const int32_t* ids,
+                                   int V_act, int k, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_head_args(h, M, d, W_act, V_act, k);
+    if (rc) return rc;
+    if (M == 0) return EVOSPEC_OK;
+    if (M > kMTile) return EVOSPEC_BAD_SHAPE;          // the split halves handle one 64-row pass
+    if (!workspace) return EVOSPEC_NULL_POINTER;
+    if (!aligned16(workspace)) return EVOSPEC_MISALIGNED;
+    if (workspace_bytes < workspace_upper_bound(V_act, k)) return EVOSPEC_WORKSPACE_TOO_SMALL;
+    int num_cu = 0;
+    rc = device_num_cu(&num_cu);
+    if (rc) return rc;
+    const Plan p = make_plan(M, V_act, k, num_cu);
+    char* ws = static_cast<char*>(workspace);
+    hipError_t e = launch_partials(p, h, M, d, W_act, ids, V_act, k, ws + p.keys_off, ws + p.stats_off,
+                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
+}
+
+int evospec_active_lmhead_merge(int M, int V_act, int d, int k, float* out_vals, int32_t* out_ids,
+                                float* out_logz, const void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || d <= 0 || (d % 8) != 0 || V_act <= 0) return EVOSPEC_BAD_SHAPE;
+    if (k < 1 || k > EVOSPEC_K_MAX || k > V_act) return EVOSPEC_BAD_K;
+    if (M == 0) return EVOSPEC_OK;
+    if (M > kMTile) return EVOSPEC_BAD_SHAPE;
+    if (!out_vals || !out_ids || !out_logz || !workspace) return EVOSPEC_NULL_POINTER;
+    if (!aligned16(workspace)) return EVOSPEC_MISALIGNED;
+    if (workspace_bytes < workspace_upper_bound(V_act, k)) return EVOSPEC_WORKSPACE_TOO_SMALL;
+    int num_cu = 0;
+    int rc = device_num_cu(&num_cu);
+    if (rc) return rc;
+    const Plan p = make_plan(M, V_act, k, num_cu);
+    const char* ws = static_cast<const char*>(workspace);
+    MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0};
+    MergeSet none{};
+    hipError_t e = launch_merge(a, none, k, out_vals, out_ids, out_logz, 0, M, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
+}
+
+int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, const int32_t* ids,
+                               int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_head_args(h, M, d, W_act, V_act, k);
+    if (rc) return rc;
+    if (M == 0) return EVOSPEC_OK;
+    if (!out_vals || !out_ids || !out_logz || !workspace) return EVOSPEC_NULL_POINTER;
+    if (!aligned16(workspace)) return EVOSPEC_MISALIGNED;
+    if (workspace_bytes < workspace_upper_bound(V_act, k)) return EVOSPEC_WORKSPACE_TOO_SMALL;
+    int num_cu = 0;
+    rc = device_num_cu(&num_cu);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    const uint16_t* hp = static_cast<const uint16_t*>(h);
+    for (int m0 = 0; m0 < M; m0 += kMTile) {            // passes of 64 draft rows share the scratch
+        const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
+        const Plan p = make_plan(rows, V_act, k, num_cu);
+        hipError_t e = launch_partials(p, hp + (size_t)m0 * d, rows, d, W_act, ids, V_act, k,
+                                       ws + p.keys_off, ws + p.stats_off, st);
+        if (e != hipSuccess) return hip_fail(e);
+        MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0};
+        MergeSet none{};
+        e = launch_merge(a, none, k, out_vals, out_ids, out_logz, m0, rows, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return EVOSPEC_OK;
+}
+
+int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void* W_core,
+                                         const int32_t* ids_core, int V_core, const void* W_arc,
+                                         const int32_t* ids_arc, int V_arc, const int32_t* row_off, int S,
+                                         int k, float* out_vals, int32_t* out_ids, float* out_logz,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || d <= 0 || (d % 8) != 0 || V_core < 0 || V_arc < 0 || V_core + V_arc <= 0 || S <= 0)
+        return EVOSPEC_BAD_SHAPE;
+    if (k < 1 || k > EVOSPEC_K_MAX || k > V_core + V_arc) return EVOSPEC_BAD_K;
+    if (!row_off) return EVOSPEC_NULL_POINTER;
+    if (row_off[0] != 0 || row_off[S] != M) return EVOSPEC_BAD_SEGMENTS;
+    for (int s = 0; s < S; ++s)
+        if (row_off[s + 1] < row_off[s]) return EVOSPEC_BAD_SEGMENTS;
+    if (M == 0) return EVOSPEC_OK;
+    if (!h || !out_vals || !out_ids || !out_logz || !workspace) return EVOSPEC_NULL_POINTER;
+    if (V_core > 0 && !W_core) return EVOSPEC_NULL_POINTER;
+    if (V_arc > 0 && (!W_arc || !ids_arc)) return EVOSPEC_NULL_POINTER;
+    if (!aligned16(h) || !aligned16(W_core) || !aligned16(W_arc) || !aligned16(workspace)) return EVOSPEC_MISALIGNED;
+    size_t need = 0;
+    evospec_workspace_bytes_segmented(M, V_core, V_arc, S, d, k, &need);
+    if (workspace_bytes < need) return EVOSPEC_WORKSPACE_TOO_SMALL;
+    int num_cu = 0;
+    int rc = device_num_cu(&num_cu);
+    if (rc) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    const uint16_t* hp = static_cast<const uint16_t*>(h);
+    const int passes = (M + kMTile - 1) / kMTile;
+    const size_t core_stride = V_core > 0 ? workspace_upper_bound(V_core, k) : 0;
+    char* ws_arc = ws + (size_t)passes * core_stride;
+    // k may exceed one of the two parts; each part's slabs then simply hold fewer candidates
+    const int k_core = k, k_arc = k;
+
+    // shared core: every 64-row pass of h against W_core, partials kept per pass
+    for (int pss = 0; pss < passes && V_core > 0; ++pss) {
+        const int m0 = pss * kMTile;
+        const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
+        const Plan p = make_plan(rows, V_core, k_core, num_cu);
+        char* w = ws + (size_t)pss * core_stride;
+        hipError_t e = launch_partials(p, hp + (size_t)m0 * d, rows, d, W_core, ids_core, V_core, k,
+                                       w + p.keys_off, w + p.stats_off, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    // per sequence: its rows against its own extension, then the merge of both partial sets.
+    // A chunk never crosses a 64-row pass boundary, so its core partials sit in one pass.
+    for (int s = 0; s < S; ++s) {
+        int m0 = row_off[s];
+        const int m_end = row_off[s + 1];
+        while (m0 < m_end) {
+            const int pass = m0 / kMTile;
+            const int pass_end = (pass + 1) * kMTile;
+            const int rows = (m_end < pass_end ? m_end : pass_end) - m0;
+            MergeSet core{}, arc{};
+            if (V_core > 0) {
+                const int pass_rows = (M - pass * kMTile) < kMTile ? (M - pass * kMTile) : kMTile;
+                const Plan pc = make_plan(pass_rows, V_core, k_core, num_cu);
+                const char* w = ws + (size_t)pass * core_stride;
+                core = MergeSet{w + pc.keys_off, w + pc.stats_off, pc.n_slabs, m0 - pass * kMTile};
+            }
+            if (V_arc > 0) {
+                const Plan pa = make_plan(rows, V_arc, k_arc, num_cu);
+                const uint16_t* Wa = static_cast<const uint16_t*>(W_arc) + (size_t)s * V_arc * d;
+                hipError_t e = launch_partials(pa, hp + (size_t)m0 * d, rows, d, Wa, ids_arc + (size_t)s * V_arc,
+                                               V_arc, k, ws_arc + pa.keys_off, ws_arc + pa.stats_off, st);
+                if (e != hipSuccess) return hip_fail(e);
+                arc = MergeSet{ws_arc + pa.keys_off, ws_arc + pa.stats_off, pa.n_slabs, 0};
+            }
+            hipError_t e = launch_merge(core, arc, k, out_vals, out_ids, out_logz, m0, rows, st);
+            if (e != hipSuccess) return hip_fail(e);
+            m0 += rows;
+        }
+    }
+    return EVOSPEC_OK;
+}
+
+int evospec_validate_ids(const int32_t* ids, int n, int V, void* stream) {
+    if (n < 0 || V <= 0) return EVOSPEC_BAD_SHAPE;
+    if (n == 0) return EVOSPEC_OK;
+    if (!ids) return EVOSPEC_NULL_POINTER;
+    int bad = 0;
+    hipError_t e = run_validate_ids(ids, n, V, static_cast<hipStream_t>(stream), &bad);
+    if (e != hipSuccess) return hip_fail(e);
+    return bad ? EVOSPEC_INVALID_IDS : EVOSPEC_OK;
+}
+
+}  // extern "C"

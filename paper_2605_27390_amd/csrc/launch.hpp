@@ -1,0 +1,27 @@
+// Launcher interface between the C ABI layer and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.hpp"
+
+namespace evospec {
+
+// One set of slab partials as the merge kernel sees it.
+struct MergeSet {
+    const void* keys = nullptr;     // u64 [n_slabs][64][k]
+    const void* stats = nullptr;    // float2 [n_slabs][64]
+    int n_slabs = 0;
+    int row_base = 0;               // slot (0..63) of the launch's first row inside the set
+};
+
+hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
+                           const int32_t* ids, int V_act, int k, void* keys, void* stats,
+                           hipStream_t stream);
+hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
+                        float* out_logz, int out_row0, int nrows, hipStream_t stream);
+hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
+                         int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream);
+hipError_t run_validate_ids(const int32_t* ids, int n, int V, hipStream_t stream, int* bad);
+
+}  // namespace evospec
