@@ -99,7 +99,8 @@ validate_ids_kernel(const int32_t* __restrict__ ids, int n, int V, int* flag) {
 // Pass 1 of the restricted head: one workgroup streams one slab of RT = 16*NW*RGW rows of
 // W_act (each wave its own 16*RGW rows, loaded from HBM straight into MFMA operand layout
 // with 128-bit loads), contracts it with up to 16*MB draft rows of h (K-chunks of h staged
-// in LDS, double buffered, shared by all waves), and reduces the slab's logits in LDS to
+// in LDS, double buffered, shared by all waves), and reduces the slab's logits, which stay in
+// the accumulators, to
 //   part_stats[slab][m] = (max_i z, sum_i exp(z - max))         over the slab's rows
 //   part_keys[slab][m][0..k) = the slab's k best keys, descending (0 = none)
 // Logits never leave the CU.
@@ -107,32 +108,30 @@ template <int NW, int RGW, int MB, bool FULLK>
 __global__ void __launch_bounds__(NW * 64)
 lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
                        const uint16_t* __restrict__ W, const int32_t* __restrict__ ids,
-                       int V_act, int k, int G,
+                       int V_act, int k, int GL,
                        u64* __restrict__ part_keys, float2* __restrict__ part_stats) {
     constexpr int NT = NW * 64;
     constexpr int RT = 16 * NW * RGW;
     constexpr int MR = 16 * MB;
-    constexpr int ZSTR = RT + 2;
     constexpr int KC = kKC;
     constexpr int KSTEPS = KC / 32;
     constexpr int HPIECES = MR * (KC / 8);
     constexpr int HP = (HPIECES + NT - 1) / NT;
 
     extern __shared__ __align__(16) unsigned char smem[];
-    // region U: h chunks during the contraction, selection scratch afterwards
+    // region U: h chunks during the contraction, the survivors' keys afterwards
     uint16_t* Hs = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* surv = reinterpret_cast<uint16_t*>(smem);                       // [MR][RT]
-    const size_t surv_bytes = align_up((size_t)MR * RT * 2, 16);
-    u64* gkey = reinterpret_cast<u64*>(smem + surv_bytes);                    // [MR][G]
-    float* gsum = reinterpret_cast<float*>(gkey + (size_t)MR * G);            // [MR][G]
-    const size_t hs_bytes = 2ull * MR * kHStride * 2;
-    const size_t sel_bytes = surv_bytes + (size_t)MR * G * 12;
-    const size_t u_bytes = align_up(hs_bytes > sel_bytes ? hs_bytes : sel_bytes, 16);
-    u64* Zk = reinterpret_cast<u64*>(smem + u_bytes);                         // [MR][ZSTR]
-    int32_t* Ids = reinterpret_cast<int32_t*>(Zk + (size_t)MR * ZSTR);        // [RT]
-    u64* tau = reinterpret_cast<u64*>(reinterpret_cast<unsigned char*>(Ids) + align_up((size_t)RT * 4, 16));  // [MR]
-    int* cnt = reinterpret_cast<int*>(tau + MR);                              // [MR]
-    float* vmax = reinterpret_cast<float*>(cnt + MR);                         // [MR]
+    u64* list = reinterpret_cast<u64*>(smem);                                 // [MR][RT]
+    constexpr size_t hs_bytes = 2ull * MR * kHStride * 2;
+    constexpr size_t list_bytes = (size_t)MR * RT * 8;
+    constexpr size_t u_bytes = align_up(hs_bytes > list_bytes ? hs_bytes : list_bytes, 16);
+    constexpr int NGS = 4 * NW;                                               // row stride of gm
+    float* gm = reinterpret_cast<float*>(smem + u_bytes);                     // [MR][NGS] group maxima
+    float* wsum = gm + (size_t)MR * NGS;                                      // [NW][MR] per-wave sum-exp
+    int32_t* Ids = reinterpret_cast<int32_t*>(wsum + (size_t)NW * MR);        // [RT]
+    float* tau = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(Ids) + align_up((size_t)RT * 4, 16));  // [MR]
+    float* vmax = tau + MR;                                                   // [MR]
+    int* cnt = reinterpret_cast<int*>(vmax + MR);                             // [MR]
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, g = lane >> 4;
@@ -161,7 +160,7 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
     const int nchunks = (d + KC - 1) / KC;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     u32x4 hreg[HP];
-    u32x4 wa[RGW][KSTEPS], wb[RGW][KSTEPS];
+    u32x4 wr[RGW][2 * KSTEPS];            // ring of W operands: k-steps of two consecutive chunks
 
     // this thread's pieces (16 B each) of an h chunk: global source, LDS destination
     gvec_ptr hsrc[HP];
@@ -200,16 +199,17 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
         for (int p = 0; p < HP; ++p)
             *reinterpret_cast<u32x4*>(Hs + (size_t)buf * MR * kHStride + hdst[p]) = hreg[p];
     };
-    auto load_w_step = [&](u32x4 (&dst)[RGW][KSTEPS], int c, int s) {
+    // k-step s (0..7) of chunk c goes to ring slot (c & 1) * KSTEPS + s
+    auto load_w_step = [&](int slot, int c, int s) {
         const int koff = c * KC + s * 32;
 #pragma unroll
         for (int rg = 0; rg < RGW; ++rg) {
             if constexpr (FULLK) {
-                dst[rg][s] = wsrc[rg][koff / 8];
+                wr[rg][slot] = wsrc[rg][koff / 8];
             } else {
                 const bool in = koff + g * 8 < d;
                 const u32x4 v = *(wsrc[rg] + ((in ? koff + g * 8 : d - 8) - g * 8) / 8);
-                dst[rg][s] = in ? v : zero4;
+                wr[rg][slot] = in ? v : zero4;
             }
         }
     };
@@ -218,146 +218,171 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
         for (int mb = 0; mb < MB; ++mb)
             b[mb] = *reinterpret_cast<const bf16x8*>(Hs + ((size_t)buf * MR + mb * 16 + n16) * kHStride + s * 32 + g * 8);
     };
-    auto mfma_step = [&](u32x4 (&cur)[RGW][KSTEPS], const bf16x8 (&b)[MB], int s) {
+    auto mfma_step = [&](int slot, const bf16x8 (&b)[MB]) {
 #pragma unroll
         for (int rg = 0; rg < RGW; ++rg) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, cur[rg][s]);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wr[rg][slot]);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
                 acc[rg][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[mb], acc[rg][mb], 0, 0, 0);
         }
     };
-    // One chunk: contract `cur` (loaded one chunk earlier) against the h chunk in LDS buffer `buf`
-    // while the next chunk's W rows stream into `nxt` and its h pieces into the other buffer.
-    // PREFETCH is a compile-time flag so that the steady-state loop has no branch in it.
-    auto chunk = [&](u32x4 (&cur)[RGW][KSTEPS], u32x4 (&nxt)[RGW][KSTEPS], int buf, int c, auto prefetch) {
-        constexpr bool PREFETCH = decltype(prefetch)::value;
+    // One chunk (8 k-steps).  Ring half `half` (= c & 1) holds this chunk's W operands, loaded two
+    // chunks ago; each slot is refilled with the same k-step of chunk c+2 right after the MFMAs
+    // that consumed it were issued, so 2*KSTEPS*RGW 16-byte loads per lane are always in flight.
+    // The h chunk c+1 is fetched into registers meanwhile and published to the other LDS buffer
+    // at the end.  PW / PH (compile time) say whether chunks c+2 / c+1 exist: the steady-state
+    // loop has no branch in it.
+    auto chunk = [&](auto half_c, int c, auto pw, auto ph) {
+        constexpr int HALF = decltype(half_c)::value;
+        constexpr bool PW = decltype(pw)::value, PH = decltype(ph)::value;
         bf16x8 b0[MB], b1[MB];
-        if constexpr (PREFETCH) load_h(c + 1);
-        load_b(b0, buf, 0);
+        if constexpr (PH) load_h(c + 1);
+        load_b(b0, HALF, 0);
 #pragma unroll
         for (int s = 0; s < KSTEPS; s += 2) {
-            if constexpr (PREFETCH) load_w_step(nxt, c + 1, s);
-            load_b(b1, buf, s + 1);
-            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs it overlaps
-            mfma_step(cur, b0, s);
-            if constexpr (PREFETCH) load_w_step(nxt, c + 1, s + 1);
-            if (s + 2 < KSTEPS) load_b(b0, buf, s + 2);
+            load_b(b1, HALF, s + 1);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step(cur, b1, s + 1);
+            mfma_step(HALF * KSTEPS + s, b0);
+            if constexpr (PW) load_w_step(HALF * KSTEPS + s, c + 2, s);
+            if (s + 2 < KSTEPS) load_b(b0, HALF, s + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(HALF * KSTEPS + s + 1, b1);
+            if constexpr (PW) load_w_step(HALF * KSTEPS + s + 1, c + 2, s + 1);
         }
-        if constexpr (PREFETCH) store_h(buf ^ 1);
+        if constexpr (PH) store_h(HALF ^ 1);
         lds_barrier();
     };
     using yes = std::true_type;
     using no = std::false_type;
+    using h0 = std::integral_constant<int, 0>;
+    using h1 = std::integral_constant<int, 1>;
 
     load_h(0);
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) load_w_step(wa, 0, s);
+    for (int s = 0; s < KSTEPS; ++s) load_w_step(s, 0, s);
+    if (nchunks > 1) {
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) load_w_step(KSTEPS + s, 1, s);
+    }
     store_h(0);
     lds_barrier();
     int c = 0;
-    for (; c + 2 < nchunks; c += 2) {           // chunks c and c+1 both have a successor
-        chunk(wa, wb, 0, c, yes{});
-        chunk(wb, wa, 1, c + 1, yes{});
+    for (; c + 4 <= nchunks; c += 2) {          // chunks c+2 and c+3 exist
+        chunk(h0{}, c, yes{}, yes{});
+        chunk(h1{}, c + 1, yes{}, yes{});
     }
-    if (nchunks - c == 2) {
-        chunk(wa, wb, 0, c, yes{});
-        chunk(wb, wa, 1, c + 1, no{});
+    const int rem = nchunks - c;                // 1, 2 or 3 chunks left
+    if (rem == 3) {
+        chunk(h0{}, c, yes{}, yes{});
+        chunk(h1{}, c + 1, no{}, yes{});
+        chunk(h0{}, c + 2, no{}, no{});
+    } else if (rem == 2) {
+        chunk(h0{}, c, no{}, yes{});
+        chunk(h1{}, c + 1, no{}, no{});
     } else {
-        chunk(wa, wb, 0, c, no{});
+        chunk(h0{}, c, no{}, no{});
     }
     // every wave is past its last read of Hs (the loop ends on a barrier): region U is free
 
-    // ---- slab epilogue: logits -> sortable keys in LDS
+    // ---- slab epilogue.  The slab's logits stay in the accumulators: lane (n16, g) holds, for each
+    // block mb of 16 draft rows, 4*RGW logits of draft row mb*16+n16 (slab rows 4g..4g+3 of each of
+    // the wave's 16-row groups).
+    if (n_valid < RT) {                                  // tail slab: rows past V_act never win
 #pragma unroll
-    for (int rg = 0; rg < RGW; ++rg) {
-        const int rl = (w * RGW + rg) * 16 + 4 * g;
-        const int4 id4 = *reinterpret_cast<const int4*>(Ids + rl);
+        for (int rg = 0; rg < RGW; ++rg)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((w * RGW + rg) * 16 + 4 * g + j >= n_valid) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) acc[rg][mb][j] = -INFINITY;
+                }
+    }
+    // (1) group maxima (level GL: lane, lane pair or wave)
+    const int NG = NW << (2 - GL);
+    {
+        const int gidx = GL == 0 ? w * 4 + g : (GL == 1 ? w * 2 + (g >> 1) : w);
+        const bool owner = GL == 0 ? true : (GL == 1 ? (g & 1) == 0 : g == 0);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const int m = mb * 16 + n16;
-            u64* dst = Zk + (size_t)m * ZSTR + rl;
-            ulonglong2 lo, hi;
-            lo.x = make_key(acc[rg][mb][0], id4.x);
-            lo.y = make_key(acc[rg][mb][1], id4.y);
-            hi.x = make_key(acc[rg][mb][2], id4.z);
-            hi.y = make_key(acc[rg][mb][3], id4.w);
-            *reinterpret_cast<ulonglong2*>(dst) = lo;
-            *reinterpret_cast<ulonglong2*>(dst + 2) = hi;
+            float lm = -INFINITY;
+#pragma unroll
+            for (int rg = 0; rg < RGW; ++rg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) lm = fmaxf(lm, acc[rg][mb][j]);
+            if (GL >= 1) lm = fmaxf(lm, __shfl_xor(lm, 16));
+            if (GL >= 2) lm = fmaxf(lm, __shfl_xor(lm, 32));
+            if (owner) gm[(mb * 16 + n16) * NGS + gidx] = lm;
         }
     }
-    if (tid < MR) { cnt[tid] = 0; tau[tid] = 0; }
+    if (tid < MR) { cnt[tid] = 0; tau[tid] = -INFINITY; }
     __syncthreads();
-
-    // ---- pass 1: maxima of G interleaved groups per draft row
-    const int npairs = rows * G;
-    for (int p = tid; p < npairs; p += NT) {
-        const int m = p / G, s = p - m * G;
-        const u64* zr = Zk + (size_t)m * ZSTR;
-        u64 mx = 0;
-        for (int i = s; i < n_valid; i += G) { const u64 v = zr[i]; mx = v > mx ? v : mx; }
-        gkey[(size_t)m * G + s] = mx;
-    }
-    __syncthreads();
-    // ---- pass 2a: tau[m] = k-th largest group maximum (a lower bound of the slab's k-th best key,
-    //      because the group maxima are G >= k distinct slab entries); vmax[m] = slab maximum
-    for (int p = tid; p < npairs; p += NT) {
-        const int m = p / G, s = p - m * G;
-        const u64* gk = gkey + (size_t)m * G;
-        const u64 mine = gk[s];
+    // (2) tau[m] = k-th largest group maximum: the group maxima are NG distinct slab entries, so at
+    //     least k entries are >= tau and nothing below tau can be among the slab's k best.
+    //     (NG < k: tau stays -inf and everything is ranked.)  vmax[m] = slab maximum.
+    for (int p = tid; p < rows * NG; p += NT) {
+        const int m = p / NG, j = p - m * NG;
+        const float* gr = gm + m * NGS;
+        const float mine = gr[j];
         int rank = 0;
-        u64 top = 0;
-        for (int j = 0; j < G; ++j) {
-            const u64 o = gk[j];
-            rank += (o > mine) || (o == mine && j < s);
-            top = o > top ? o : top;
+        float top = -INFINITY;
+        for (int i = 0; i < NG; ++i) {
+            const float o = gr[i];
+            rank += (o > mine) || (o == mine && i < j);
+            top = fmaxf(top, o);
         }
         if (rank == k - 1) tau[m] = mine;
-        if (s == 0) vmax[m] = key_value(top);
+        if (j == 0) vmax[m] = top;
     }
     __syncthreads();
-    // ---- pass 2b: keep entries >= tau (at least k of them if the slab has k), sum exp(z - vmax)
-    for (int p = tid; p < npairs; p += NT) {
-        const int m = p / G, s = p - m * G;
-        const u64* zr = Zk + (size_t)m * ZSTR;
-        const u64 t = tau[m];
-        const float vm = vmax[m];
-        float sum = 0.f;
-        for (int i = s; i < n_valid; i += G) {
-            const u64 v = zr[i];
-            sum += __expf(key_value(v) - vm);
-            if (v >= t) {
-                const int pos = atomicAdd(&cnt[m], 1);
-                surv[(size_t)m * RT + pos] = (uint16_t)i;
-            }
+    // (3) sum of exponentials; entries >= tau become candidates (key = logit and full-vocabulary id)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = mb * 16 + n16;
+        if (mb * 16 < rows) {                                // uniform: skip blocks of padding draft rows
+            const bool live = m < rows;
+            const float t = live ? tau[m] : INFINITY;
+            const float vm = live ? vmax[m] : 0.f;
+            float se = 0.f;
+#pragma unroll
+            for (int rg = 0; rg < RGW; ++rg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float x = acc[rg][mb][j];
+                    const int rl = (w * RGW + rg) * 16 + 4 * g + j;
+                    se += __expf(x - vm);
+                    if (x >= t && rl < n_valid) {
+                        const int pos = atomicAdd(&cnt[m], 1);
+                        list[(size_t)m * RT + pos] = make_key(x, Ids[rl]);
+                    }
+                }
+            se += __shfl_xor(se, 16);
+            se += __shfl_xor(se, 32);
+            if (g == 0) wsum[w * MR + m] = se;
         }
-        gsum[(size_t)m * G + s] = sum;
     }
     __syncthreads();
-    // ---- pass 3: exact rank among the survivors; write the k best, the stats
-    const size_t out_row = (size_t)blockIdx.x * kMTile;
-    for (int p = tid; p < rows * n_valid; p += NT) {
-        const int m = p / n_valid, q = p - m * n_valid;
+    // (4) exact order among the candidates of a draft row (NW threads per row); the k best go out
+    if (tid < rows * NW) {
+        const int m = tid / NW, sub = tid - m * NW;
         const int c = cnt[m];
-        if (q >= c) continue;
-        const u64* zr = Zk + (size_t)m * ZSTR;
-        const uint16_t* sv = surv + (size_t)m * RT;
-        const u64 mine = zr[sv[q]];
-        int rank = 0;
-        for (int j = 0; j < c; ++j) {
-            const u64 o = zr[sv[j]];
-            rank += (o > mine) || (o == mine && j < q);
+        const u64* lst = list + (size_t)m * RT;
+        u64* outk = part_keys + ((size_t)blockIdx.x * kMTile + m) * k;
+        for (int q = sub; q < c; q += NW) {
+            const u64 mine = lst[q];
+            int rank = 0;
+            for (int j = 0; j < c; ++j) {
+                const u64 o = lst[j];
+                rank += (o > mine) || (o == mine && j < q);
+            }
+            if (rank < k) outk[rank] = mine;
         }
-        u64* outk = part_keys + (out_row + m) * k;
-        if (rank < k) outk[rank] = mine;
-        if (q == 0) {
+        if (sub == 0) {
             for (int j = c; j < k; ++j) outk[j] = 0;               // slab holds fewer than k rows
-            const float* gs = gsum + (size_t)m * G;
             float sum = 0.f;
-            for (int j = 0; j < G; ++j) sum += gs[j];
-            part_stats[out_row + m] = make_float2(vmax[m], sum);
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) sum += wsum[ww * MR + m];
+            part_stats[(size_t)blockIdx.x * kMTile + m] = make_float2(vmax[m], sum);
         }
     }
 }
@@ -366,106 +391,127 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
 // Pass 2: one workgroup per draft row merges the slab partials:
 //   logZ = M + log(sum_t s_t * exp(m_t - M)),  M = max_t m_t
 //   top-k = the k largest of all slab candidates (keys are unique, so the order is total).
-// Candidates come from up to two partial sets (a shared core and a per-sequence extension
-// in the batched variant).  The candidate stream is filtered against the running k-th best
-// and merged in batches by exact rank counting.
+// Candidates come from up to two partial sets (a shared core and a per-sequence extension in the
+// batched variant).  Every slab's list is sorted, so its head is its maximum: per block of 256
+// lists the k-th largest head (together with the running result) bounds the answer from below,
+// at most k lists reach above that bound, and only their entries are ranked exactly.
 struct PartialSet {
     const u64* keys;        // [n_slabs][64][k]
     const float2* stats;    // [n_slabs][64]
     int n_slabs;
-    int row_base;           // draft row of this launch's block 0 inside the set's 64-row pass
+    int row_base;           // slot of this launch's block 0 inside the set's 64-row pass
 };
 
 constexpr int kMergeThreads = 256;
+
+__device__ __forceinline__ u64 wave_bcast(u64 x, int src_lane /*uniform*/) {
+    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)x, src_lane);
+    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), src_lane);
+    return ((u64)hi << 32) | lo;
+}
 
 __global__ void __launch_bounds__(kMergeThreads)
 lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
                     float* __restrict__ out_vals, int32_t* __restrict__ out_ids,
                     float* __restrict__ out_logz, int out_row0) {
     constexpr int NT = kMergeThreads;
-    __shared__ u64 run[2][kKMax];
-    __shared__ u64 pend[2 * NT + kKMax];
+    constexpr int NWV = NT / 64;
+    __shared__ u64 run[2][kKMax];                    // running k best, descending
+    __shared__ u64 cand[(NWV + 1) * kKMax];          // per-wave best heads, then the running list
+    __shared__ u64 pend[kKMax * kKMax + kKMax];      // entries that reach the bound
+    __shared__ u64 tau_s;
     __shared__ int npend;
-    __shared__ float red_m[NT], red_s[NT];
+    __shared__ float wave_m[NWV], wave_s[NWV];
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int out_row = out_row0 + blockIdx.x;
+    const int slotA = A.row_base + blockIdx.x, slotB = B.row_base + blockIdx.x;
+    const int total = A.n_slabs + B.n_slabs;
 
-    // ---- log-normaliser
-    float mx = -INFINITY;
-    for (int set = 0; set < 2; ++set) {
-        const PartialSet& P = set ? B : A;
-        const int slot = P.row_base + blockIdx.x;
-        for (int t = tid; t < P.n_slabs; t += NT) mx = fmaxf(mx, P.stats[(size_t)t * kMTile + slot].x);
+    // ---- log-normaliser: online (max, scaled sum) per thread, fixed-shape reduction
+    float mx = -INFINITY, sm = 0.f;
+    for (int t = tid; t < total; t += NT) {
+        const float2 st = t < A.n_slabs ? A.stats[(size_t)t * kMTile + slotA]
+                                        : B.stats[(size_t)(t - A.n_slabs) * kMTile + slotB];
+        const float nm = fmaxf(mx, st.x);
+        sm = (mx == -INFINITY ? 0.f : sm * __expf(mx - nm)) + st.y * __expf(st.x - nm);
+        mx = nm;
     }
-    red_m[tid] = mx;
-    __syncthreads();
-    for (int o = NT / 2; o > 0; o >>= 1) {
-        if (tid < o) red_m[tid] = fmaxf(red_m[tid], red_m[tid + o]);
-        __syncthreads();
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float om = __shfl_xor(mx, o), os = __shfl_xor(sm, o);
+        const float nm = fmaxf(mx, om);
+        sm = (mx == -INFINITY ? 0.f : sm * __expf(mx - nm)) + (om == -INFINITY ? 0.f : os * __expf(om - nm));
+        mx = nm;
     }
-    const float gmax = red_m[0];
-    float sum = 0.f;
-    for (int set = 0; set < 2; ++set) {
-        const PartialSet& P = set ? B : A;
-        const int slot = P.row_base + blockIdx.x;
-        for (int t = tid; t < P.n_slabs; t += NT) {
-            const float2 st = P.stats[(size_t)t * kMTile + slot];
-            sum += st.y * __expf(st.x - gmax);
-        }
-    }
-    red_s[tid] = sum;
-    __syncthreads();
-    for (int o = NT / 2; o > 0; o >>= 1) {
-        if (tid < o) red_s[tid] += red_s[tid + o];
-        __syncthreads();
-    }
-    if (tid == 0) out_logz[out_row] = gmax + __logf(red_s[0]);
-
-    // ---- top-k over all candidates
+    if (lane == 0) { wave_m[w] = mx; wave_s[w] = sm; }
     if (tid == 0) npend = 0;
-    int nrun = 0;            // entries in run[cur], sorted descending
-    int cur = 0;
-    u64 thr = 0;             // current k-th best (0 until k candidates were seen)
     __syncthreads();
+    if (tid == 0) {
+        float gm_ = wave_m[0], gs = wave_s[0];
+        for (int i = 1; i < NWV; ++i) {
+            const float nm = fmaxf(gm_, wave_m[i]);
+            gs = (gm_ == -INFINITY ? 0.f : gs * __expf(gm_ - nm)) + (wave_m[i] == -INFINITY ? 0.f : wave_s[i] * __expf(wave_m[i] - nm));
+            gm_ = nm;
+        }
+        out_logz[out_row] = gm_ + __logf(gs);
+    }
 
-    auto flush = [&]() {
-        // merge run[cur][0..nrun) with pend[0..npend) into run[cur^1]; all threads call it
+    // ---- top-k
+    int nrun = 0, cur = 0;
+    u64 thr = 0;                                     // running k-th best (0 until k entries are known)
+    for (int base = 0; base < total; base += NT) {
+        const int L = base + tid;
+        const u64* lst = nullptr;
+        if (L < total)
+            lst = L < A.n_slabs ? A.keys + ((size_t)L * kMTile + slotA) * k
+                                : B.keys + ((size_t)(L - A.n_slabs) * kMTile + slotB) * k;
+        u64 head = lst ? lst[0] : 0;
+        if (head <= thr) head = 0;                   // cannot improve the running result
+        // (1) rank of this list's head among the wave's 64 heads; the wave's k best go to cand
+        int rank = 0;
+        for (int j = 0; j < 64; ++j) {
+            const u64 o = wave_bcast(head, j);
+            rank += (o > head) || (o == head && j < lane);
+        }
+        if (rank < k) cand[w * k + rank] = head;
+        if (tid < nrun) cand[NWV * k + tid] = run[cur][tid];
+        __syncthreads();
+        // (2) bound = k-th largest of (wave bests + running list): k real candidates are >= it
+        const int ne = NWV * k + nrun;
+        for (int e = tid; e < ne; e += NT) {
+            const u64 mine = cand[e];
+            int r = 0;
+            for (int j = 0; j < ne; ++j) { const u64 o = cand[j]; r += (o > mine) || (o == mine && j < e); }
+            if (r == k - 1) tau_s = mine;
+        }
+        __syncthreads();
+        // (3) lists (at most k of them) and running entries that reach the bound feed pend
+        const u64 t = tau_s;
+        if (head != 0 && head >= t) {
+            for (int j = 0; j < k; ++j) {
+                const u64 key = lst[j];
+                if (key == 0 || key < t) break;      // lists are sorted
+                pend[atomicAdd(&npend, 1)] = key;
+            }
+        }
+        if (tid < nrun && run[cur][tid] >= t) pend[atomicAdd(&npend, 1)] = run[cur][tid];
+        __syncthreads();
+        // (4) exact order among pend -> new running list
         const int np = npend;
-        const int total = nrun + np;
-        for (int e = tid; e < total; e += NT) {
-            const u64 mine = e < nrun ? run[cur][e] : pend[e - nrun];
-            int rank = 0;
-            for (int j = 0; j < nrun; ++j) { const u64 o = run[cur][j]; rank += (o > mine) || (o == mine && j < e); }
-            for (int j = 0; j < np; ++j) { const u64 o = pend[j]; rank += (o > mine) || (o == mine && j + nrun < e); }
-            if (rank < k) run[cur ^ 1][rank] = mine;
+        for (int e = tid; e < np; e += NT) {
+            const u64 mine = pend[e];
+            int r = 0;
+            for (int j = 0; j < np; ++j) { const u64 o = pend[j]; r += (o > mine) || (o == mine && j < e); }
+            if (r < k) run[cur ^ 1][r] = mine;
         }
         __syncthreads();
         cur ^= 1;
-        nrun = total < k ? total : k;
+        nrun = np < k ? np : k;
         thr = nrun == k ? run[cur][k - 1] : 0;
         if (tid == 0) npend = 0;
         __syncthreads();
-    };
-
-    for (int set = 0; set < 2; ++set) {
-        const PartialSet& P = set ? B : A;
-        const int slot = P.row_base + blockIdx.x;
-        const int ncand = P.n_slabs * k;
-        for (int base = 0; base < ncand; base += NT) {
-            const int c = base + tid;
-            if (c < ncand) {
-                const int t = c / k, j = c - t * k;
-                const u64 key = P.keys[((size_t)t * kMTile + slot) * k + j];
-                if (key > thr) pend[atomicAdd(&npend, 1)] = key;
-            }
-            __syncthreads();
-            const int np_now = npend;        // same value in every thread ...
-            __syncthreads();                 // ... because nobody appends before all have read it
-            if (np_now > NT) flush();
-        }
     }
-    if (npend > 0) flush();                  // uniform: no append since the last barrier
     for (int j = tid; j < k; j += NT) {
         const u64 key = j < nrun ? run[cur][j] : 0;
         out_vals[(size_t)out_row * k + j] = key ? key_value(key) : -INFINITY;
@@ -514,7 +560,7 @@ hipError_t launch_partials_k(const Plan& p, const void* h, int rows, int d, cons
     }
     hipLaunchKernelGGL(kern, dim3(p.n_slabs), dim3(NW * 64), p.lds_bytes, stream,
                        static_cast<const uint16_t*>(h), rows, d, static_cast<const uint16_t*>(W), ids,
-                       V_act, k, p.groups, static_cast<u64*>(keys), static_cast<float2*>(stats));
+                       V_act, k, p.gl, static_cast<u64*>(keys), static_cast<float2*>(stats));
     return hipGetLastError();
 }
 

@@ -29,7 +29,7 @@ struct Plan {
     int mb = 0;              // 16-row blocks of draft rows held in accumulators (1, 2 or 4)
     int rt = 0;              // slab rows
     int n_slabs = 0;
-    int groups = 0;          // selection groups per draft row in the slab epilogue (>= k)
+    int gl = 0;              // selection group level of the slab epilogue (see group_level_for)
     size_t lds_bytes = 0;
     // workspace layout (bytes from the workspace base), for one pass of <= 64 draft rows
     size_t keys_off = 0, stats_off = 0, total_bytes = 0;
@@ -39,29 +39,28 @@ constexpr size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 inline int mb_for_rows(int rows) { return rows <= 16 ? 1 : (rows <= 32 ? 2 : 4); }
 
-inline int groups_for(int rows, int k, int nthreads, int rt) {
-    // number of (row, group) pairs ~ a whole number of thread rounds; at least k groups so
-    // that the k-th largest group maximum bounds the slab's k-th best from below
-    int rounds = (k * rows + nthreads - 1) / nthreads;
-    int g = rounds * nthreads / rows;
-    int cap = k > 32 ? k : 32;
-    if (g > cap) g = cap;
-    if (g > rt / 2) g = rt / 2;
-    if (g < k) g = k;
-    return g;
+// Granularity of the selection groups in the slab epilogue.  A slab's logits for one draft row
+// sit 4*rgw per lane in 4*nw lanes; level 0 takes each lane as a group, level 1 pairs of lanes,
+// level 2 whole wavefronts (nw groups).  The k-th largest group maximum is a lower bound of the
+// slab's k-th best logit, so only entries at or above it need exact ranking.  Coarser groups cost
+// less to rank and filter almost as well: take the coarsest level with at least 1.5 k groups.
+inline int group_level_for(int k, int nw) {
+    const int want = k + k / 2;
+    if (nw >= want) return 2;
+    if (2 * nw >= want) return 1;
+    return 0;
 }
 
-inline size_t lds_bytes_for(int nw, int rgw, int mb, int groups) {
+inline size_t lds_bytes_for(int nw, int rgw, int mb) {
     const int rt = 16 * nw * rgw;
     const int mrows = 16 * mb;
-    size_t hs = 2ull * mrows * kHStride * 2;                               // h chunk, double buffered
-    size_t sel = align_up((size_t)mrows * rt * 2, 16)                      // survivor indices (u16)
-               + (size_t)mrows * groups * 8                                // group maxima (keys)
-               + (size_t)mrows * groups * 4;                               // group sum-exp
-    size_t u = hs > sel ? hs : sel;                                        // the two never live together
-    size_t zk = (size_t)mrows * (rt + 2) * 8;                              // slab logits as sortable keys
-    size_t small = align_up((size_t)rt * 4, 16) + (size_t)mrows * 4 * 4;   // ids, counters, tau, vmax
-    return align_up(u, 16) + align_up(zk, 16) + small;
+    size_t hs = 2ull * mrows * kHStride * 2;                 // h chunk, double buffered
+    size_t list = (size_t)mrows * rt * 8;                    // surviving keys per draft row
+    size_t u = hs > list ? hs : list;                        // the two never live together
+    size_t gm = (size_t)mrows * 4 * nw * 4;                  // group maxima
+    size_t wsum = (size_t)nw * mrows * 4;                    // per-wave sum-exp
+    size_t small = align_up((size_t)rt * 4, 16) + (size_t)mrows * 3 * 4;   // ids, tau, vmax, counters
+    return align_up(u, 16) + gm + wsum + small;
 }
 
 // Slab shape for V_act rows on a device with `num_cu` compute units: fewest row-rounds
@@ -74,15 +73,14 @@ inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, in
         const int nw = kShapes[i].nw, rgw = kShapes[i].rgw;
         const int rt = 16 * nw * rgw;
         const int n_slabs = (V_act + rt - 1) / rt;
-        const int g = groups_for(rows, k, nw * 64, rt);
-        const size_t lds = lds_bytes_for(nw, rgw, mb, g);
+        const size_t lds = lds_bytes_for(nw, rgw, mb);
         if (lds > (size_t)kLdsLimit) continue;
         const long rounds = (n_slabs + num_cu - 1) / num_cu;
         const long cost = rounds * rt;
         if (best_cost < 0 || cost < best_cost || (cost == best_cost && rt > best.rt)) {
             best_cost = cost;
             best.nw = nw; best.rgw = rgw; best.mb = mb; best.rt = rt; best.n_slabs = n_slabs;
-            best.groups = g; best.lds_bytes = lds;
+            best.gl = group_level_for(k, nw); best.lds_bytes = lds;
         }
     }
     best.keys_off = 0;
