@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the active-vocabulary LM head on one MI355X.
+
+A step is one pass of the whole hot path on one batch of synthetic input:
+  1. a dynamic-buffer update -- `evospec_active_gather` of 32 new rows into ARC slots of the
+     compact matrix (the paper caps insertions at 32 per failure event), then
+  2. `evospec_active_lmhead_topk`: restricted projection + log-normaliser + top-k + id remap.
+All inputs are resident in HBM before the timed region.  Steps rotate over several copies of
+W_act so that every step streams its weights from HBM rather than from the memory-side cache.
+
+Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: this build is a
+single-GPU kernel path.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+METRIC = "active LM-head+top-k µs/step & HBM GB/s (d=4096, V_act=36864, M=60)"
+UPDATE_ROWS = 32                # App. "Additional safeguards": at most 32 insertions per failure event
+
+
+def algorithmic_bytes(V_act: int, d: int, M: int, k: int) -> int:
+    """Bytes the method must move per step: each active weight row once, h, ids, outputs."""
+    return V_act * d * 2 + M * d * 2 + V_act * 4 + M * (8 * k + 4)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="draft60", choices=["draft60", "tiny"])
+    ap.add_argument("--copies", type=int, default=4, help="distinct W_act copies rotated over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a single-GPU kernel path; --gpus must be 1 "
+              "(how the path would shard is described in DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import evospec_inputs as gi
+    import paper_2605_27390_amd as ev
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    c = gi.CONFIGS[args.config]
+    V, d, M, k = c["V"], c["d"], c["M"], c["k"]
+    n_core, n_arc = c["n_core"], c["n_arc"]
+    V_act = n_core + n_arc
+    R = max(1, args.copies)
+    K, Wm = args.steps, args.warmup
+
+    def log(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    # ---------------------------------------------------------------- inputs (host -> HBM)
+    t0 = time.time()
+    W_lm_bits = gi.gen_W_lm(V, d)
+    h_bits = gi.gen_h(M, d, gi.SEED_H + c["cfg"])
+    ids0 = gi.active_ids(args.config)
+    log(f"generated W_lm {W_lm_bits.shape}, h, ids in {time.time() - t0:.1f}s; "
+        f"checksums W={gi.checksum(W_lm_bits):016x} h={gi.checksum(h_bits):016x} ids={gi.checksum(ids0):016x}")
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    W_lm = dev_bf16(W_lm_bits)
+    h = dev_bf16(h_bits)
+    ids_dev = torch.from_numpy(ids0).to(dev)
+    W_acts = [torch.empty((V_act, d), dtype=torch.bfloat16, device=dev) for _ in range(R)]
+    act_ids = [torch.empty((V_act,), dtype=torch.int32, device=dev) for _ in range(R)]
+    for r in range(R):
+        ev.active_gather(W_lm, ids_dev, None, W_acts[r], act_ids[r])      # full rebuild = the same call
+    # the sequence of dynamic-buffer updates every copy goes through (host bookkeeping only)
+    n_updates = (K + Wm) // R + 2
+    upd_slots, upd_ids = [], []
+    state = ids0.copy()
+    if n_arc >= UPDATE_ROWS:
+        for u in range(n_updates):
+            s_, n_ = gi.arc_update(V, state, n_core, UPDATE_ROWS, seed=7000 + u)
+            state[s_] = n_
+            upd_slots.append(torch.from_numpy(s_).to(dev))
+            upd_ids.append(torch.from_numpy(n_).to(dev))
+    ws = torch.empty(ev.workspace_bytes(M, V_act, d, k), dtype=torch.uint8, device=dev)
+    out_v = torch.empty((M, k), dtype=torch.float32, device=dev)
+    out_i = torch.empty((M, k), dtype=torch.int32, device=dev)
+    out_l = torch.empty((M,), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    def step(i):
+        r = i % R
+        if upd_slots:
+            u = i // R
+            ev.active_gather(W_lm, upd_ids[u], upd_slots[u], W_acts[r], act_ids[r])
+        ev.active_lmhead_topk(h, W_acts[r], act_ids[r], k, out_v, out_i, out_l, ws)
+
+    # ---------------------------------------------------------------- timed region
+    for i in range(Wm):
+        step(i)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(Wm, Wm + K):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_s * 1e3 / K
+    us_step = ms_per_step * 1e3
+    alg_bytes = algorithmic_bytes(V_act, d, M, k)
+
+    # ---------------------------------------------------------------- dominant kernel alone
+    # (the slab kernel that streams W_act; HIP events on the launch stream, same rotation)
+    def timed(fn, iters, warm=10):
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(iters):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / iters          # us
+
+    n_ev = max(20, min(K, 200))
+    part_us = timed(lambda i: ev.active_lmhead_partials(h, W_acts[i % R], act_ids[i % R], k, ws), n_ev)
+    merge_us = timed(lambda i: ev.active_lmhead_merge(M, V_act, d, k, out_v, out_i, out_l, ws), n_ev)
+    head_us = timed(lambda i: ev.active_lmhead_topk(h, W_acts[i % R], act_ids[i % R], k, out_v, out_i, out_l, ws), n_ev)
+    roof = {
+        "kernel": "lmhead_partials_kernel",
+        "bound": "hbm",
+        "achieved": round(alg_bytes / part_us / 1e3, 1),       # GB/s
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": round(alg_bytes / part_us / 1e3 / HBM_PEAK_GBPS, 4),
+        "traffic": None,
+        "avg_kernel_us": round(part_us, 2),
+        "algorithmic_bytes": alg_bytes,
+    }
+    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.config}.json")
+    if os.path.exists(tfile):
+        try:
+            roof["traffic"] = json.load(open(tfile)).get("bytes_per_launch")
+        except Exception:
+            pass
+
+    extra = {"partials_us": round(part_us, 2), "merge_us": round(merge_us, 2), "head_us": round(head_us, 2),
+             "event_us_per_step": round(ev_ms * 1e3 / K, 2), "copies": R,
+             "rows_per_s": round(M / (us_step * 1e-6), 1),
+             "hbm_gbps_step": round(alg_bytes / us_step / 1e3, 1),
+             "hbm_frac_step": round(alg_bytes / us_step / 1e3 / HBM_PEAK_GBPS, 4)}
+    if not args.no_extras and args.config == "draft60":
+        # cache-warm figure (one copy), update kernels alone, and the unpruned head on the same GPU
+        extra["head_us_cache_warm"] = round(timed(
+            lambda i: ev.active_lmhead_topk(h, W_acts[0], act_ids[0], k, out_v, out_i, out_l, ws), n_ev), 2)
+        if upd_slots:
+            extra["gather32_us"] = round(timed(
+                lambda i: ev.active_gather(W_lm, upd_ids[0], upd_slots[0], W_acts[0], act_ids[0]), n_ev), 2)
+        extra["gather_full_us"] = round(timed(
+            lambda i: ev.active_gather(W_lm, ids_dev, None, W_acts[i % R], act_ids[i % R]), 20, warm=3), 2)
+        ws_full = torch.empty(ev.workspace_bytes(M, V, d, k), dtype=torch.uint8, device=dev)
+        full_us = timed(lambda i: ev.active_lmhead_topk(h, W_lm, None, k, out_v, out_i, out_l, ws_full), 30, warm=5)
+        extra["fullvocab_head_us"] = round(full_us, 2)
+        extra["speedup_vs_fullvocab"] = round(full_us / head_us, 3)
+        extra["fullvocab_hbm_gbps"] = round(algorithmic_bytes(V, d, M, k) / full_us / 1e3, 1)
+
+    # ---------------------------------------------------------------- CPU oracle on the host cores
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        # the state of copy 0 after the timed steps is whatever it is: re-run one head on a fresh
+        # copy of the initial active set so that GPU output and oracle see the same rows
+        ev.active_gather(W_lm, ids_dev, None, W_acts[0], act_ids[0])
+        ev.active_lmhead_topk(h, W_acts[0], act_ids[0], k, out_v, out_i, out_l, ws)
+        torch.cuda.synchronize()
+        gv, gi_, gl = out_v.cpu().numpy(), out_i.cpu().numpy(), out_l.cpu().numpy()
+        W_act_host = W_lm_bits[ids0]
+        t0 = time.perf_counter()
+        ov, oi, ol = oracle.active_lmhead_topk(h_bits, W_act_host, ids0, k + 1)
+        cpu_s = time.perf_counter() - t0
+        cpu = {"value": round(cpu_s * 1e6, 1), "unit": "us/step", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"one full head step (all {V_act} active rows x {M} draft rows, fp64), no gather"}
+        gap = np.abs(ov[:, k - 1] - ov[:, k]) / np.maximum(np.abs(ov[:, k - 1]), np.abs(ov[:, k]))
+        clear = gap > 1e-3
+        same = np.array([set(gi_[m]) == set(oi[m, :k]) for m in range(M)])
+        extra["parity"] = {
+            "logz_max_rel_err": float(np.max(np.abs(gl - ol) / np.abs(ol))),
+            "top1_max_abs_err": float(np.max(np.abs(gv[:, 0] - ov[:, 0]))),
+            "rows_with_clear_gap": int(clear.sum()),
+            "id_sets_equal_on_clear_rows": bool(np.all(same[clear])),
+            "near_tie_rows_exempt": int((~clear).sum()),
+        }
+
+    line = {
+        "metric": METRIC if args.config == "draft60" else f"active LM-head+top-k us/step ({args.config})",
+        "value": round(us_step, 2),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: d={d}, V={V}, V_act={V_act} ({n_core} core + {n_arc} ARC), M={M}, k={k}, "
+                               f"{UPDATE_ROWS if upd_slots else 0}-row ARC update per step"},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "extra": extra,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

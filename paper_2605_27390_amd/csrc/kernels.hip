@@ -104,7 +104,7 @@ validate_ids_kernel(const int32_t* __restrict__ ids, int n, int V, int* flag) {
 //   part_stats[slab][m] = (max_i z, sum_i exp(z - max))         over the slab's rows
 //   part_keys[slab][m][0..k) = the slab's k best keys, descending (0 = none)
 // Logits never leave the CU.
-template <int NW, int RGW, int MB, bool FULLK>
+template <int NW, int RGW, int RC, int MB, bool FULLK>
 __global__ void __launch_bounds__(NW * 64)
 lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
                        const uint16_t* __restrict__ W, const int32_t* __restrict__ ids,
@@ -160,7 +160,7 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
     const int nchunks = (d + KC - 1) / KC;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     u32x4 hreg[HP];
-    u32x4 wr[RGW][2 * KSTEPS];            // ring of W operands: k-steps of two consecutive chunks
+    u32x4 wr[RGW][RC * KSTEPS];           // ring of W operands: k-steps of RC consecutive chunks
 
     // this thread's pieces (16 B each) of an h chunk: global source, LDS destination
     gvec_ptr hsrc[HP];
@@ -199,7 +199,7 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
         for (int p = 0; p < HP; ++p)
             *reinterpret_cast<u32x4*>(Hs + (size_t)buf * MR * kHStride + hdst[p]) = hreg[p];
     };
-    // k-step s (0..7) of chunk c goes to ring slot (c & 1) * KSTEPS + s
+    // k-step s (0..7) of chunk c goes to ring slot (c % RC) * KSTEPS + s
     auto load_w_step = [&](int slot, int c, int s) {
         const int koff = c * KC + s * 32;
 #pragma unroll
@@ -227,62 +227,60 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
                 acc[rg][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[mb], acc[rg][mb], 0, 0, 0);
         }
     };
-    // One chunk (8 k-steps).  Ring half `half` (= c & 1) holds this chunk's W operands, loaded two
-    // chunks ago; each slot is refilled with the same k-step of chunk c+2 right after the MFMAs
-    // that consumed it were issued, so 2*KSTEPS*RGW 16-byte loads per lane are always in flight.
+    // One chunk (8 k-steps).  Ring part SLOT (= c % RC) holds this chunk's W operands, loaded RC
+    // chunks ago; each slot is refilled with the same k-step of chunk c+RC right after the MFMAs
+    // that consumed it were issued, so RC*KSTEPS*RGW 16-byte loads per lane stay in flight.
     // The h chunk c+1 is fetched into registers meanwhile and published to the other LDS buffer
-    // at the end.  PW / PH (compile time) say whether chunks c+2 / c+1 exist: the steady-state
-    // loop has no branch in it.
-    auto chunk = [&](auto half_c, int c, auto pw, auto ph) {
-        constexpr int HALF = decltype(half_c)::value;
-        constexpr bool PW = decltype(pw)::value, PH = decltype(ph)::value;
+    // at the end.  In the steady state (chunks c+1 and c+RC exist) there is no branch in here;
+    // the last chunks test for them at run time.
+    auto chunk = [&](auto slot_c, int c, auto steady) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        constexpr bool STEADY = decltype(steady)::value;
+        const bool pw = STEADY || (c + RC < nchunks);
+        const bool ph = STEADY || (c + 1 < nchunks);
+        const int buf = c & 1;
         bf16x8 b0[MB], b1[MB];
-        if constexpr (PH) load_h(c + 1);
-        load_b(b0, HALF, 0);
+        if (ph) load_h(c + 1);
+        load_b(b0, buf, 0);
 #pragma unroll
         for (int s = 0; s < KSTEPS; s += 2) {
-            load_b(b1, HALF, s + 1);
+            load_b(b1, buf, s + 1);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step(HALF * KSTEPS + s, b0);
-            if constexpr (PW) load_w_step(HALF * KSTEPS + s, c + 2, s);
-            if (s + 2 < KSTEPS) load_b(b0, HALF, s + 2);
+            mfma_step(SLOT * KSTEPS + s, b0);
+            if (pw) load_w_step(SLOT * KSTEPS + s, c + RC, s);
+            if (s + 2 < KSTEPS) load_b(b0, buf, s + 2);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step(HALF * KSTEPS + s + 1, b1);
-            if constexpr (PW) load_w_step(HALF * KSTEPS + s + 1, c + 2, s + 1);
+            mfma_step(SLOT * KSTEPS + s + 1, b1);
+            if (pw) load_w_step(SLOT * KSTEPS + s + 1, c + RC, s + 1);
         }
-        if constexpr (PH) store_h(HALF ^ 1);
+        if (ph) store_h(buf ^ 1);
         lds_barrier();
     };
-    using yes = std::true_type;
-    using no = std::false_type;
-    using h0 = std::integral_constant<int, 0>;
-    using h1 = std::integral_constant<int, 1>;
+    // RC consecutive chunks starting at `base` (a multiple of RC), ring parts 0..RC-1
+    auto chunk_group = [&](int base, auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
+#define EVOSPEC_CHUNK(I)                                                                   \
+        if constexpr (I < RC) {                                                            \
+            if (STEADY || base + I < nchunks) chunk(std::integral_constant<int, I>{}, base + I, steady); \
+        }
+        EVOSPEC_CHUNK(0) EVOSPEC_CHUNK(1) EVOSPEC_CHUNK(2) EVOSPEC_CHUNK(3)
+#undef EVOSPEC_CHUNK
+    };
+    static_assert(RC >= 1 && RC <= 4, "ring depth");
 
     load_h(0);
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) load_w_step(s, 0, s);
-    if (nchunks > 1) {
+    for (int i = 0; i < RC; ++i) {
+        if (i < nchunks) {
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) load_w_step(KSTEPS + s, 1, s);
+            for (int s = 0; s < KSTEPS; ++s) load_w_step(i * KSTEPS + s, i, s);
+        }
     }
     store_h(0);
     lds_barrier();
     int c = 0;
-    for (; c + 4 <= nchunks; c += 2) {          // chunks c+2 and c+3 exist
-        chunk(h0{}, c, yes{}, yes{});
-        chunk(h1{}, c + 1, yes{}, yes{});
-    }
-    const int rem = nchunks - c;                // 1, 2 or 3 chunks left
-    if (rem == 3) {
-        chunk(h0{}, c, yes{}, yes{});
-        chunk(h1{}, c + 1, no{}, yes{});
-        chunk(h0{}, c + 2, no{}, no{});
-    } else if (rem == 2) {
-        chunk(h0{}, c, no{}, yes{});
-        chunk(h1{}, c + 1, no{}, no{});
-    } else {
-        chunk(h0{}, c, no{}, no{});
-    }
+    for (; c + 2 * RC <= nchunks; c += RC) chunk_group(c, std::true_type{});     // every prefetch target exists
+    for (; c < nchunks; c += RC) chunk_group(c, std::false_type{});
     // every wave is past its last read of Hs (the loop ends on a barrier): region U is free
 
     // ---- slab epilogue.  The slab's logits stay in the accumulators: lane (n16, g) holds, for each
@@ -530,24 +528,11 @@ namespace evospec {
 namespace {
 constexpr int kMaxDevices = 64;
 
-template <int NW, int RGW, int MB, bool FULLK>
-hipError_t launch_partials_k(const Plan& p, const void* h, int rows, int d, const void* W,
-                             const int32_t* ids, int V_act, int k, void* keys, void* stats,
-                             hipStream_t stream);
-
-template <int NW, int RGW, int MB>
-hipError_t launch_partials_t(const Plan& p, const void* h, int rows, int d, const void* W,
-                             const int32_t* ids, int V_act, int k, void* keys, void* stats,
-                             hipStream_t stream) {
-    if (d % kKC == 0) return launch_partials_k<NW, RGW, MB, true>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
-    return launch_partials_k<NW, RGW, MB, false>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
-}
-
-template <int NW, int RGW, int MB, bool FULLK>
+template <int NW, int RGW, int RC, int MB, bool FULLK>
 hipError_t launch_partials_k(const Plan& p, const void* h, int rows, int d, const void* W,
                              const int32_t* ids, int V_act, int k, void* keys, void* stats,
                              hipStream_t stream) {
-    auto kern = lmhead_partials_kernel<NW, RGW, MB, FULLK>;
+    auto kern = lmhead_partials_kernel<NW, RGW, RC, MB, FULLK>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -564,27 +549,28 @@ hipError_t launch_partials_k(const Plan& p, const void* h, int rows, int d, cons
     return hipGetLastError();
 }
 
-template <int NW, int RGW>
-hipError_t launch_partials_mb(const Plan& p, const void* h, int rows, int d, const void* W,
-                              const int32_t* ids, int V_act, int k, void* keys, void* stats,
-                              hipStream_t stream) {
-    switch (p.mb) {
-        case 1: return launch_partials_t<NW, RGW, 1>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
-        case 2: return launch_partials_t<NW, RGW, 2>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
-        case 4: return launch_partials_t<NW, RGW, 4>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
-        default: return hipErrorInvalidValue;
-    }
+template <int NW, int RGW, int RC>
+hipError_t launch_partials_shape(const Plan& p, const void* h, int rows, int d, const void* W,
+                                 const int32_t* ids, int V_act, int k, void* keys, void* stats,
+                                 hipStream_t stream) {
+    const bool full = d % kKC == 0;
+#define EVOSPEC_MB(MB_)                                                                              \
+    if (p.mb == MB_)                                                                                 \
+        return full ? launch_partials_k<NW, RGW, RC, MB_, true>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream)   \
+                    : launch_partials_k<NW, RGW, RC, MB_, false>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
+    EVOSPEC_MB(1) EVOSPEC_MB(2) EVOSPEC_MB(4)
+#undef EVOSPEC_MB
+    return hipErrorInvalidValue;
 }
 }  // namespace
 
 hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
                            const int32_t* ids, int V_act, int k, void* keys, void* stats,
                            hipStream_t stream) {
-#define EVOSPEC_SHAPE(NW_, RGW_)                                                               \
-    if (p.nw == NW_ && p.rgw == RGW_)                                                          \
-        return launch_partials_mb<NW_, RGW_>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
-    EVOSPEC_SHAPE(4, 1) EVOSPEC_SHAPE(5, 1) EVOSPEC_SHAPE(6, 1) EVOSPEC_SHAPE(7, 1) EVOSPEC_SHAPE(8, 1)
-    EVOSPEC_SHAPE(9, 1) EVOSPEC_SHAPE(10, 1) EVOSPEC_SHAPE(12, 1) EVOSPEC_SHAPE(8, 2)
+#define EVOSPEC_SHAPE(NW_, RGW_, RC_)                                                          \
+    if (p.nw == NW_ && p.rgw == RGW_ && p.rc == RC_)                                           \
+        return launch_partials_shape<NW_, RGW_, RC_>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
+    EVOSPEC_SLAB_SHAPES(EVOSPEC_SHAPE)
 #undef EVOSPEC_SHAPE
     return hipErrorInvalidValue;
 }

@@ -19,13 +19,20 @@ constexpr int kHStride = kKC + 8;   // LDS row stride of the h chunk (bf16 eleme
 constexpr int kRowsMinSlab = 64;    // smallest slab any plan uses (workspace upper bound)
 constexpr int kLdsLimit = 160 * 1024;
 
-struct SlabShape { int nw; int rgw; };
-// Slab shapes that have a compiled kernel.  RT = 16 * nw * rgw.
-constexpr SlabShape kShapes[] = {{4, 1}, {5, 1}, {6, 1}, {7, 1}, {8, 1}, {9, 1}, {10, 1}, {12, 1}, {8, 2}};
+// Slab shapes that have a compiled kernel: X(nw, rgw, rc) with nw wavefronts per workgroup, rgw
+// 16-row groups per wavefront (RT = 16 * nw * rgw rows per slab) and a W-operand ring of rc chunks
+// of kKC hidden elements per lane.  (Measured on MI355X: more waves per CU beat a deeper ring per wave.)
+#define EVOSPEC_SLAB_SHAPES(X) \
+    X(4, 1, 2) X(5, 1, 2) X(6, 1, 2) X(7, 1, 2) X(8, 1, 2) X(9, 1, 2) X(10, 1, 2) X(12, 1, 2)
+struct SlabShape { int nw; int rgw; int rc; };
+#define EVOSPEC_SHAPE_ENTRY(NW_, RGW_, RC_) {NW_, RGW_, RC_},
+constexpr SlabShape kShapes[] = {EVOSPEC_SLAB_SHAPES(EVOSPEC_SHAPE_ENTRY)};
+#undef EVOSPEC_SHAPE_ENTRY
 constexpr int kNumShapes = sizeof(kShapes) / sizeof(kShapes[0]);
 
 struct Plan {
     int nw = 0, rgw = 0;     // wavefronts per workgroup, 16-row groups per wavefront
+    int rc = 0;              // chunks in the W-operand ring
     int mb = 0;              // 16-row blocks of draft rows held in accumulators (1, 2 or 4)
     int rt = 0;              // slab rows
     int n_slabs = 0;
@@ -79,7 +86,7 @@ inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, in
         const long cost = rounds * rt;
         if (best_cost < 0 || cost < best_cost || (cost == best_cost && rt > best.rt)) {
             best_cost = cost;
-            best.nw = nw; best.rgw = rgw; best.mb = mb; best.rt = rt; best.n_slabs = n_slabs;
+            best.nw = nw; best.rgw = rgw; best.rc = kShapes[i].rc; best.mb = mb; best.rt = rt; best.n_slabs = n_slabs;
             best.gl = group_level_for(k, nw); best.lds_bytes = lds;
         }
     }
