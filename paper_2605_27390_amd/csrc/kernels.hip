@@ -25,8 +25,8 @@ typedef const u32x4 __attribute__((address_space(1))) * gvec_ptr;   // 16-byte l
 // (logit, id) -> one 64-bit key whose unsigned order is "larger logit first, then smaller
 // full-vocabulary id".  Key 0 is reserved for "no candidate".
 __device__ __forceinline__ uint32_t f32_to_ordered(float f) {
-    uint32_t u = __float_as_uint(f + 0.0f);             // -0 -> +0 so that the two tie
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    const uint32_t u = __float_as_uint(f + 0.0f);       // -0 -> +0 so that the two tie
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);   // negative: flip all bits, else the sign
 }
 __device__ __forceinline__ float ordered_to_f32(uint32_t o) {
     return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
@@ -138,10 +138,11 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
     const int row0 = blockIdx.x * RT;
     const int n_valid = min(RT, V_act - row0);
 
-    for (int i = tid; i < RT; i += NT) {
-        const int r = row0 + i;
-        Ids[i] = (r < V_act) ? (ids ? ids[r] : r) : 0x7fffffff;
-    }
+    // full-vocabulary id of slab row `tid` (RT <= NT): loaded first, parked in LDS once the operand
+    // loads of the first chunks have been issued
+    static_assert(RT <= NT, "one slab row per thread");
+    int id_reg = 0x7fffffff;
+    if (tid < RT && row0 + tid < V_act) id_reg = ids ? ids[row0 + tid] : row0 + tid;
 
     const uint16_t* wp[RGW];
 #pragma unroll
@@ -276,6 +277,8 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
             for (int s = 0; s < KSTEPS; ++s) load_w_step(i * KSTEPS + s, i, s);
         }
     }
+    for (int i = tid; i < MR * NGS; i += NT) gm[i] = -INFINITY;      // padding of the group-maximum rows
+    if (tid < RT) Ids[tid] = id_reg;
     store_h(0);
     lds_barrier();
     int c = 0;
@@ -315,52 +318,82 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
     }
     if (tid < MR) { cnt[tid] = 0; tau[tid] = -INFINITY; }
     __syncthreads();
-    // (2) tau[m] = k-th largest group maximum: the group maxima are NG distinct slab entries, so at
-    //     least k entries are >= tau and nothing below tau can be among the slab's k best.
-    //     (NG < k: tau stays -inf and everything is ranked.)  vmax[m] = slab maximum.
-    for (int p = tid; p < rows * NG; p += NT) {
-        const int m = p / NG, j = p - m * NG;
-        const float* gr = gm + m * NGS;
-        const float mine = gr[j];
-        int rank = 0;
-        float top = -INFINITY;
-        for (int i = 0; i < NG; ++i) {
-            const float o = gr[i];
-            rank += (o > mine) || (o == mine && i < j);
-            top = fmaxf(top, o);
+    // (2) tau[m] = k-th largest group maximum (counting equal values): the group maxima are NG
+    //     distinct slab entries, so at least k entries are >= tau and nothing below tau can be among
+    //     the slab's k best.  (NG < k: tau stays -inf and everything is ranked.)  vmax[m] = slab
+    //     maximum.  Rows of gm are padded with -inf to a multiple of 4 and read 16 bytes at a time.
+    {
+        const int ng4 = (NG + 3) >> 2;
+        for (int p = tid; p < rows * NG; p += NT) {
+            const int m = p / NG, j = p - m * NG;
+            const float4* gr4 = reinterpret_cast<const float4*>(gm + m * NGS);
+            const float mine = gm[m * NGS + j];
+            int gt = 0, ge = 0;
+            float top = -INFINITY;
+            for (int i4 = 0; i4 < ng4; ++i4) {
+                const float4 o = gr4[i4];
+                gt += (o.x > mine) + (o.y > mine) + (o.z > mine) + (o.w > mine);
+                ge += (o.x >= mine) + (o.y >= mine) + (o.z >= mine) + (o.w >= mine);
+                top = fmaxf(fmaxf(top, fmaxf(o.x, o.y)), fmaxf(o.z, o.w));
+            }
+            if (gt < k && ge >= k) tau[m] = mine;            // equal maxima write the same value
+            if (j == 0) vmax[m] = top;
         }
-        if (rank == k - 1) tau[m] = mine;
-        if (j == 0) vmax[m] = top;
     }
     __syncthreads();
-    // (3) sum of exponentials; entries >= tau become candidates (key = logit and full-vocabulary id)
+    // (3) sum of exponentials; entries >= tau become candidates (key = logit and full-vocabulary id).
+    //     One LDS atomic per lane and draft-row block reserves room for the lane's candidates, which
+    //     are then stored without branches or dependent loads.
+    {
+        int4 id4[RGW];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int m = mb * 16 + n16;
-        if (mb * 16 < rows) {                                // uniform: skip blocks of padding draft rows
-            const bool live = m < rows;
-            const float t = live ? tau[m] : INFINITY;
-            const float vm = live ? vmax[m] : 0.f;
-            float se = 0.f;
+        for (int rg = 0; rg < RGW; ++rg) id4[rg] = *reinterpret_cast<const int4*>(Ids + (w * RGW + rg) * 16 + 4 * g);
+        uint32_t pick[MB];
+        int base[MB];
 #pragma unroll
-            for (int rg = 0; rg < RGW; ++rg)
+        for (int mb = 0; mb < MB; ++mb) {
+            const int m = mb * 16 + n16;
+            pick[mb] = 0;
+            if (mb * 16 < rows) {                            // uniform: skip blocks of padding draft rows
+                const bool live = m < rows;
+                const float t = live ? tau[m] : INFINITY;
+                const float vm = live ? vmax[m] : 0.f;
+                float se = 0.f;
+#pragma unroll
+                for (int rg = 0; rg < RGW; ++rg)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float x = acc[rg][mb][j];
+                        const int rl = (w * RGW + rg) * 16 + 4 * g + j;
+                        se += __expf(x - vm);
+                        pick[mb] |= (x >= t && rl < n_valid) ? 1u << (rg * 4 + j) : 0u;
+                    }
+                se += __shfl_xor(se, 16);
+                se += __shfl_xor(se, 32);
+                if (g == 0) wsum[w * MR + m] = se;
+            }
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            base[mb] = pick[mb] ? atomicAdd(&cnt[mb * 16 + n16], __popc(pick[mb])) : 0;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            u64* dst = list + (size_t)(mb * 16 + n16) * RT + base[mb];
+#pragma unroll
+            for (int rg = 0; rg < RGW; ++rg) {
+                const int idv[4] = {id4[rg].x, id4[rg].y, id4[rg].z, id4[rg].w};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float x = acc[rg][mb][j];
-                    const int rl = (w * RGW + rg) * 16 + 4 * g + j;
-                    se += __expf(x - vm);
-                    if (x >= t && rl < n_valid) {
-                        const int pos = atomicAdd(&cnt[m], 1);
-                        list[(size_t)m * RT + pos] = make_key(x, Ids[rl]);
-                    }
+                    const int e = rg * 4 + j;
+                    const u64 key = make_key(acc[rg][mb][j], idv[j]);
+                    if (pick[mb] >> e & 1u) dst[__popc(pick[mb] & ((1u << e) - 1u))] = key;
                 }
-            se += __shfl_xor(se, 16);
-            se += __shfl_xor(se, 32);
-            if (g == 0) wsum[w * MR + m] = se;
+            }
         }
     }
     __syncthreads();
-    // (4) exact order among the candidates of a draft row (NW threads per row); the k best go out
+    // (4) exact order among the candidates of a draft row (NW threads per row); the k best go out.
+    //     Keys are distinct because ids are, so a key's rank is the number of larger keys.
     if (tid < rows * NW) {
         const int m = tid / NW, sub = tid - m * NW;
         const int c = cnt[m];
@@ -369,10 +402,13 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
         for (int q = sub; q < c; q += NW) {
             const u64 mine = lst[q];
             int rank = 0;
-            for (int j = 0; j < c; ++j) {
-                const u64 o = lst[j];
-                rank += (o > mine) || (o == mine && j < q);
+            int j = 0;
+            for (; j + 4 <= c; j += 4) {
+                const ulonglong2 a = *reinterpret_cast<const ulonglong2*>(lst + j);
+                const ulonglong2 b2 = *reinterpret_cast<const ulonglong2*>(lst + j + 2);
+                rank += (a.x > mine) + (a.y > mine) + (b2.x > mine) + (b2.y > mine);
             }
+            for (; j < c; ++j) rank += lst[j] > mine;
             if (rank < k) outk[rank] = mine;
         }
         if (sub == 0) {
@@ -416,9 +452,11 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
     constexpr int NWV = NT / 64;
     __shared__ u64 run[2][kKMax];                    // running k best, descending
     __shared__ u64 cand[(NWV + 1) * kKMax];          // per-wave best heads, then the running list
-    __shared__ u64 pend[kKMax * kKMax + kKMax];      // entries that reach the bound
+    constexpr int kPendCap = kKMax * kKMax + kKMax;
+    __shared__ u64 pend[kPendCap];                   // entries that reach the bound
+    __shared__ const u64* qual[kKMax];             // lists whose head reaches the bound
     __shared__ u64 tau_s;
-    __shared__ int npend;
+    __shared__ int npend, nqual;
     __shared__ float wave_m[NWV], wave_s[NWV];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -443,7 +481,7 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
         mx = nm;
     }
     if (lane == 0) { wave_m[w] = mx; wave_s[w] = sm; }
-    if (tid == 0) npend = 0;
+    if (tid == 0) { npend = 0; nqual = 0; }
     __syncthreads();
     if (tid == 0) {
         float gm_ = wave_m[0], gs = wave_s[0];
@@ -480,34 +518,37 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
         for (int e = tid; e < ne; e += NT) {
             const u64 mine = cand[e];
             int r = 0;
-            for (int j = 0; j < ne; ++j) { const u64 o = cand[j]; r += (o > mine) || (o == mine && j < e); }
+            for (int j = 0; j < ne; ++j) { const u64 o = cand[j]; r += (o > mine) || (o == mine && j < e); }   // zeros tie: keep the index order
             if (r == k - 1) tau_s = mine;
         }
         __syncthreads();
-        // (3) lists (at most k of them) and running entries that reach the bound feed pend
+        // (3) lists (at most k of them) and running entries that reach the bound feed pend; the
+        //     qualifying lists are read by all threads at once (one entry per thread and round)
         const u64 t = tau_s;
-        if (head != 0 && head >= t) {
-            for (int j = 0; j < k; ++j) {
-                const u64 key = lst[j];
-                if (key == 0 || key < t) break;      // lists are sorted
-                pend[atomicAdd(&npend, 1)] = key;
-            }
-        }
+        // (capacity checks only matter if the caller broke the unique-id precondition)
+        if (head != 0 && head >= t) { const int qi = atomicAdd(&nqual, 1); if (qi < kKMax) qual[qi] = lst; }
         if (tid < nrun && run[cur][tid] >= t) pend[atomicAdd(&npend, 1)] = run[cur][tid];
         __syncthreads();
+        const int nq = nqual < kKMax ? nqual : kKMax;
+        for (int e = tid; e < nq * k; e += NT) {
+            const int li = e / k, j = e - li * k;
+            const u64 key = qual[li][j];
+            if (key != 0 && key >= t) { const int pi = atomicAdd(&npend, 1); if (pi < kPendCap) pend[pi] = key; }
+        }
+        __syncthreads();
         // (4) exact order among pend -> new running list
-        const int np = npend;
+        const int np = npend < kPendCap ? npend : kPendCap;
         for (int e = tid; e < np; e += NT) {
             const u64 mine = pend[e];
             int r = 0;
-            for (int j = 0; j < np; ++j) { const u64 o = pend[j]; r += (o > mine) || (o == mine && j < e); }
+            for (int j = 0; j < np; ++j) r += pend[j] > mine;
             if (r < k) run[cur ^ 1][r] = mine;
         }
         __syncthreads();
         cur ^= 1;
         nrun = np < k ? np : k;
         thr = nrun == k ? run[cur][k - 1] : 0;
-        if (tid == 0) npend = 0;
+        if (tid == 0) { npend = 0; nqual = 0; }
         __syncthreads();
     }
     for (int j = tid; j < k; j += NT) {
