@@ -1,0 +1,133 @@
+"""GPU parity at the benchmark's full sizes (Qwen3-8B / EAGLE-2 shapes), in the launch
+configuration bench.py times.  The oracle computes every logit at these sizes in seconds on the
+host cores (OpenMP), except for the batched case, where it checks a sample of rows per sequence."""
+import numpy as np
+import pytest
+
+import evospec_inputs as gi
+from helpers import bf16_dev_to_bits, check_head, to_dev_bf16, to_dev_i32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ev():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2605_27390_amd as ev
+    return ev
+
+
+@pytest.fixture(scope="module")
+def lm_head():
+    """The full synthetic LM head (151,936 x 4,096 bf16), host bits and device tensor."""
+    c = gi.CONFIGS["draft60"]
+    bits = gi.gen_W_lm(c["V"], c["d"])
+    return bits, to_dev_bf16(bits)
+
+
+def test_draft60_step_with_update(ev, oracle_mod, lm_head):
+    """Config 2: gather of the 36,864-id active set, a 32-row ARC update, then the head."""
+    import torch
+    W_bits, W_lm = lm_head
+    c = gi.CONFIGS["draft60"]
+    V, d, M, k = c["V"], c["d"], c["M"], c["k"]
+    ids = gi.active_ids("draft60")
+    V_act = ids.shape[0]
+    h = gi.gen_h(M, d, gi.SEED_H + 2)
+    W_act = torch.empty((V_act, d), dtype=torch.bfloat16, device="cuda")
+    act_ids = torch.empty((V_act,), dtype=torch.int32, device="cuda")
+    ev.active_gather(W_lm, to_dev_i32(ids), None, W_act, act_ids)
+    slots, new_ids = gi.arc_update(V, ids, c["n_core"], 32, seed=7000)
+    ev.active_gather(W_lm, to_dev_i32(new_ids), to_dev_i32(slots), W_act, act_ids)
+    ref_ids = ids.copy()
+    ref_ids[slots] = new_ids
+    v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act, act_ids, k)
+    torch.cuda.synchronize()
+    assert np.array_equal(act_ids.cpu().numpy(), ref_ids)
+    assert ev.validate_ids(act_ids, V)
+    # gathered rows are bit-exact (sampled slots incl. the updated ones; the whole matrix via a checksum)
+    sample = np.concatenate([slots, np.random.default_rng(0).choice(V_act, 256, replace=False)])
+    got = bf16_dev_to_bits(W_act[torch.from_numpy(sample).cuda().long()])
+    assert np.array_equal(got, W_bits[ref_ids[sample]])
+    assert gi.checksum(bf16_dev_to_bits(W_act)) == gi.checksum(W_bits[ref_ids])
+    _, _, _, z = oracle_mod.active_lmhead_topk(h, W_bits[ref_ids], ref_ids, k, return_logits=True)
+    st = check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, ref_ids, k, "draft60")
+    assert st["max_abs_err"] < 1e-4
+    assert st["exempt_rows"] < M // 2
+
+
+@pytest.mark.parametrize("M", [1, 4, 8])
+def test_depth_expansion_rows(ev, oracle_mod, lm_head, M):
+    """Config 3: 16,384 core + 2,048 ARC ids, M in {1, 4, 8} rows, with a 256-row update."""
+    import torch
+    W_bits, W_lm = lm_head
+    c = gi.CONFIGS["depth"]
+    V, d, k = c["V"], c["d"], c["k"]
+    ids = gi.active_ids("depth")
+    V_act = ids.shape[0]
+    assert V_act == 18432
+    h = gi.gen_h(M, d, gi.SEED_H + 30 + M)
+    W_act = torch.empty((V_act, d), dtype=torch.bfloat16, device="cuda")
+    act_ids = torch.empty((V_act,), dtype=torch.int32, device="cuda")
+    ev.active_gather(W_lm, to_dev_i32(ids), None, W_act, act_ids)
+    slots, new_ids = gi.arc_update(V, ids, c["n_core"], c["update_rows"], seed=7100 + M)
+    ev.active_gather(W_lm, to_dev_i32(new_ids), to_dev_i32(slots), W_act, act_ids)
+    ref_ids = ids.copy()
+    ref_ids[slots] = new_ids
+    v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act, act_ids, k)
+    torch.cuda.synchronize()
+    assert gi.checksum(bf16_dev_to_bits(W_act)) == gi.checksum(W_bits[ref_ids])
+    z = oracle_mod.logits(h, W_bits[ref_ids])
+    check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, ref_ids, k, f"depth M={M}")
+
+
+def test_full_vocabulary_head(ev, oracle_mod, lm_head):
+    """Config 4: the unpruned head (ids = NULL, W_act = W_lm) -- also Eq. 1 as printed."""
+    import torch
+    W_bits, W_lm = lm_head
+    c = gi.CONFIGS["fullvocab"]
+    M, k = c["M"], c["k"]
+    h = gi.gen_h(M, c["d"], gi.SEED_H + 4)
+    v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_lm, None, k)
+    torch.cuda.synchronize()
+    z = oracle_mod.logits(h, W_bits)
+    check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, None, k, "fullvocab")
+    # the pruned head's logZ is below the full one, and its top-k is the full top-k filtered to active ids
+    ids = gi.active_ids("draft60")
+    v2, i2, l2 = ev.active_lmhead_topk(to_dev_bf16(h), to_dev_bf16(W_bits[ids]), to_dev_i32(ids), k)
+    torch.cuda.synchronize()
+    assert np.all(l2.cpu().numpy() < l.cpu().numpy())
+    check_head(v2.cpu().numpy(), i2.cpu().numpy(), l2.cpu().numpy(), z[:, ids], ids, k, "pruned-vs-full")
+
+
+def test_batched_serving(ev, oracle_mod, lm_head):
+    """Config 5: 16 sequences x 60 rows, shared 32,768-id core + 2,048 ARC ids per sequence.
+    The oracle checks 4 rows of every sequence (first, last and two inside)."""
+    import torch
+    W_bits, W_lm = lm_head
+    c = gi.CONFIGS["batched"]
+    V, d, M, k, S, rps = c["V"], c["d"], c["M"], c["k"], c["S"], c["rows_per_seq"]
+    core, arcs = gi.batched_ids(V, c["n_core"], c["n_arc"], S)
+    h = gi.gen_h(M, d, gi.SEED_H + 5)
+    row_off = np.arange(S + 1, dtype=np.int32) * rps
+    W_core = torch.empty((core.shape[0], d), dtype=torch.bfloat16, device="cuda")
+    ids_core = torch.empty((core.shape[0],), dtype=torch.int32, device="cuda")
+    ev.active_gather(W_lm, to_dev_i32(core), None, W_core, ids_core)
+    W_arc = torch.empty((S * arcs.shape[1], d), dtype=torch.bfloat16, device="cuda")
+    ids_arc = torch.empty((S * arcs.shape[1],), dtype=torch.int32, device="cuda")
+    ev.active_gather(W_lm, to_dev_i32(arcs.reshape(-1)), None, W_arc, ids_arc)
+    v, i, l = ev.active_lmhead_topk_segmented(to_dev_bf16(h), W_core, ids_core, W_arc.view(S, arcs.shape[1], d),
+                                              ids_arc.view(S, arcs.shape[1]), row_off, k)
+    torch.cuda.synchronize()
+    v, i, l = v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy()
+    assert np.isfinite(v).all() and np.isfinite(l).all() and (i >= 0).all()
+    for s in range(S):
+        union = np.concatenate([core, arcs[s]])
+        rows = row_off[s] + np.array([0, 17, 41, rps - 1])
+        z = oracle_mod.logits(h[rows], W_bits[union])
+        check_head(v[rows], i[rows], l[rows], z, union, k, f"batched seq {s}")
+        # every returned id of the sequence's other rows is at least a member of its own union
+        member = np.zeros(V, dtype=bool)
+        member[union] = True
+        assert member[i[row_off[s]:row_off[s + 1]]].all()
