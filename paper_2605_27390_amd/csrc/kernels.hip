@@ -464,6 +464,13 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
     const int slotA = A.row_base + blockIdx.x, slotB = B.row_base + blockIdx.x;
     const int total = A.n_slabs + B.n_slabs;
 
+    auto list_of = [&](int L) -> const u64* {
+        return L < A.n_slabs ? A.keys + ((size_t)L * kMTile + slotA) * k
+                             : B.keys + ((size_t)(L - A.n_slabs) * kMTile + slotB) * k;
+    };
+    // the first block's list heads are fetched together with the statistics (one memory round trip)
+    const u64 head_first = tid < total ? list_of(tid)[0] : 0;
+
     // ---- log-normaliser: online (max, scaled sum) per thread, fixed-shape reduction
     float mx = -INFINITY, sm = 0.f;
     for (int t = tid; t < total; t += NT) {
@@ -498,11 +505,8 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
     u64 thr = 0;                                     // running k-th best (0 until k entries are known)
     for (int base = 0; base < total; base += NT) {
         const int L = base + tid;
-        const u64* lst = nullptr;
-        if (L < total)
-            lst = L < A.n_slabs ? A.keys + ((size_t)L * kMTile + slotA) * k
-                                : B.keys + ((size_t)(L - A.n_slabs) * kMTile + slotB) * k;
-        u64 head = lst ? lst[0] : 0;
+        const u64* lst = L < total ? list_of(L) : nullptr;
+        u64 head = base == 0 ? head_first : (lst ? lst[0] : 0);
         if (head <= thr) head = 0;                   // cannot improve the running result
         // (1) rank of this list's head among the wave's 64 heads; the wave's k best go to cand
         int rank = 0;
