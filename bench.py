@@ -184,6 +184,49 @@ def main() -> int:
         extra["fullvocab_head_us"] = round(full_us, 2)
         extra["speedup_vs_fullvocab"] = round(full_us / head_us, 3)
         extra["fullvocab_hbm_gbps"] = round(algorithmic_bytes(V, d, M, k) / full_us / 1e3, 1)
+        del ws_full
+        # per-depth tree expansion: 16,384 core + 2,048 ARC ids, M in {1, 4, 8}, and a 256-row update
+        cd = gi.CONFIGS["depth"]
+        ids_d = gi.active_ids("depth")
+        Vd = ids_d.shape[0]
+        ids_d_dev = torch.from_numpy(ids_d).to(dev)
+        Wd = [torch.empty((Vd, d), dtype=torch.bfloat16, device=dev) for _ in range(8)]
+        idd = [torch.empty((Vd,), dtype=torch.int32, device=dev) for _ in range(8)]
+        for r in range(8):
+            ev.active_gather(W_lm, ids_d_dev, None, Wd[r], idd[r])
+        s_, n_ = gi.arc_update(V, ids_d, cd["n_core"], cd["update_rows"], seed=7100)
+        s_dev, n_dev = torch.from_numpy(s_).to(dev), torch.from_numpy(n_).to(dev)
+        depth = {"gather256_us": round(timed(lambda i: ev.active_gather(W_lm, n_dev, s_dev, Wd[i % 8], idd[i % 8]), n_ev), 2)}
+        for Md in cd["Ms"]:
+            hd = dev_bf16(gi.gen_h(Md, d, gi.SEED_H + 30 + Md))
+            ov_, oi_, ol_ = (torch.empty((Md, k), dtype=torch.float32, device=dev),
+                             torch.empty((Md, k), dtype=torch.int32, device=dev),
+                             torch.empty((Md,), dtype=torch.float32, device=dev))
+            us = timed(lambda i: ev.active_lmhead_topk(hd, Wd[i % 8], idd[i % 8], k, ov_, oi_, ol_, ws), n_ev)
+            depth[f"head_us_M{Md}"] = round(us, 2)
+            depth[f"hbm_gbps_M{Md}"] = round(algorithmic_bytes(Vd, d, Md, k) / us / 1e3, 1)
+        extra["depth_V18432"] = depth
+        del Wd, idd
+        # batched serving: 16 sequences x 60 rows, shared 32,768-id core + 2,048 ARC ids per sequence
+        cb = gi.CONFIGS["batched"]
+        core_b, arcs_b = gi.batched_ids(V, cb["n_core"], cb["n_arc"], cb["S"])
+        Mb, S_, Va = cb["M"], cb["S"], cb["n_arc"]
+        W_core = torch.empty((cb["n_core"], d), dtype=torch.bfloat16, device=dev)
+        ids_core = torch.empty((cb["n_core"],), dtype=torch.int32, device=dev)
+        ev.active_gather(W_lm, torch.from_numpy(core_b).to(dev), None, W_core, ids_core)
+        W_arc = torch.empty((S_ * Va, d), dtype=torch.bfloat16, device=dev)
+        ids_arc = torch.empty((S_ * Va,), dtype=torch.int32, device=dev)
+        ev.active_gather(W_lm, torch.from_numpy(arcs_b.reshape(-1)).to(dev), None, W_arc, ids_arc)
+        hb = dev_bf16(gi.gen_h(Mb, d, gi.SEED_H + 5))
+        row_off = [s * cb["rows_per_seq"] for s in range(S_ + 1)]
+        ws_b = torch.empty(ev.workspace_bytes_segmented(Mb, cb["n_core"], Va, S_, d, k), dtype=torch.uint8, device=dev)
+        seg_us = timed(lambda i: ev.active_lmhead_topk_segmented(hb, W_core, ids_core, W_arc.view(S_, Va, d),
+                                                                 ids_arc.view(S_, Va), row_off, k, ws_b), 10, warm=2)
+        flops = 2.0 * d * (Mb * cb["n_core"] + Mb * Va)
+        extra["batched_M960"] = {"head_us": round(seg_us, 1), "tflops": round(flops / seg_us / 1e6, 1),
+                                 "mfma_frac_bf16": round(flops / seg_us / 1e6 / 2500.0, 4),
+                                 "rows_per_s": round(Mb / (seg_us * 1e-6), 1)}
+        del W_core, W_arc, ws_b
 
     # ---------------------------------------------------------------- CPU oracle on the host cores
     cpu = None
