@@ -45,6 +45,14 @@ int check_head_args(const void* h, int M, int d, const void* W, int V_act, int k
     return EVOSPEC_OK;
 }
 
+// Scratch for the shared core of the segmented head: one set of partials per 64-row pass, or
+// the large-M layout from kGemmMinRows rows on.
+size_t core_workspace_bytes(int M, int d, int V_core, int k) {
+    if (evospec::use_gemm(M, d)) return evospec::make_gemm_plan(M, V_core, k).total_bytes;
+    const size_t passes = ((size_t)M + evospec::kMTile - 1) / evospec::kMTile;
+    return passes * evospec::workspace_upper_bound(V_core, k);
+}
+
 }  // namespace
 
 using namespace evospec;
@@ -74,7 +82,9 @@ int evospec_workspace_bytes(int M, int V_act, int d, int k, size_t* out_bytes) {
     if (!out_bytes) return EVOSPEC_NULL_POINTER;
     if (M < 0 || d <= 0 || (d % 8) != 0 || V_act <= 0) return EVOSPEC_BAD_SHAPE;
     if (k < 1 || k > EVOSPEC_K_MAX || k > V_act) return EVOSPEC_BAD_K;
-    *out_bytes = workspace_upper_bound(V_act, k);      // passes over M reuse the same scratch
+    size_t need = workspace_upper_bound(V_act, k);     // passes over M reuse the same scratch
+    if (use_gemm(M, d)) need = make_gemm_plan(M, V_act, k).total_bytes;     // one launch for all rows
+    *out_bytes = need;
     return EVOSPEC_OK;
 }
 
@@ -83,10 +93,10 @@ int evospec_workspace_bytes_segmented(int M, int V_core, int V_arc, int S, int d
     if (M < 0 || d <= 0 || (d % 8) != 0 || V_core < 0 || V_arc < 0 || V_core + V_arc <= 0 || S <= 0)
         return EVOSPEC_BAD_SHAPE;
     if (k < 1 || k > EVOSPEC_K_MAX || k > V_core + V_arc) return EVOSPEC_BAD_K;
-    // core partials are kept for every 64-row pass; the extension scratch is reused per chunk
-    const size_t passes = ((size_t)M + kMTile - 1) / kMTile;
+    // core partials are kept for every draft row (per 64-row pass, or one large-M launch); the
+    // extension scratch is reused per chunk
     size_t total = 0;
-    if (V_core > 0) total += passes * workspace_upper_bound(V_core, k);
+    if (V_core > 0) total += core_workspace_bytes(M, d, V_core, k);
     if (V_arc > 0) total += workspace_upper_bound(V_arc, k);
     *out_bytes = total > 0 ? total : 256;
     return EVOSPEC_OK;
@@ -137,7 +147,7 @@ int evospec_active_lmhead_merge(int M, int V_act, int d, int k, float* out_vals,
     if (rc) return rc;
     const Plan p = make_plan(M, V_act, k, num_cu);
     const char* ws = static_cast<const char*>(workspace);
-    MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0};
+    MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0, kMTile};
     MergeSet none{};
     hipError_t e = launch_merge(a, none, k, out_vals, out_ids, out_logz, 0, M, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
@@ -151,20 +161,31 @@ int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, c
     if (M == 0) return EVOSPEC_OK;
     if (!out_vals || !out_ids || !out_logz || !workspace) return EVOSPEC_NULL_POINTER;
     if (!aligned16(workspace)) return EVOSPEC_MISALIGNED;
-    if (workspace_bytes < workspace_upper_bound(V_act, k)) return EVOSPEC_WORKSPACE_TOO_SMALL;
+    size_t need = 0;
+    evospec_workspace_bytes(M, V_act, d, k, &need);
+    if (workspace_bytes < need) return EVOSPEC_WORKSPACE_TOO_SMALL;
     int num_cu = 0;
     rc = device_num_cu(&num_cu);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     const uint16_t* hp = static_cast<const uint16_t*>(h);
+    if (use_gemm(M, d)) {                               // bound by the contraction: all rows at once
+        const GemmPlan gp = make_gemm_plan(M, V_act, k);
+        hipError_t e = launch_gemm_partials(h, M, d, W_act, ids, V_act, k, ws + gp.keys_off, ws + gp.stats_off, st);
+        if (e != hipSuccess) return hip_fail(e);
+        MergeSet a{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M};
+        MergeSet none{};
+        e = launch_merge(a, none, k, out_vals, out_ids, out_logz, 0, M, st);
+        return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
+    }
     for (int m0 = 0; m0 < M; m0 += kMTile) {            // passes of 64 draft rows share the scratch
         const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
         const Plan p = make_plan(rows, V_act, k, num_cu);
         hipError_t e = launch_partials(p, hp + (size_t)m0 * d, rows, d, W_act, ids, V_act, k,
                                        ws + p.keys_off, ws + p.stats_off, st);
         if (e != hipSuccess) return hip_fail(e);
-        MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0};
+        MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0, kMTile};
         MergeSet none{};
         e = launch_merge(a, none, k, out_vals, out_ids, out_logz, m0, rows, st);
         if (e != hipSuccess) return hip_fail(e);
@@ -199,9 +220,17 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     const uint16_t* hp = static_cast<const uint16_t*>(h);
-    const int passes = (M + kMTile - 1) / kMTile;
+    const bool gemm_core = V_core > 0 && use_gemm(M, d);
+    const int passes = gemm_core ? 0 : (M + kMTile - 1) / kMTile;
     const size_t core_stride = V_core > 0 ? workspace_upper_bound(V_core, k) : 0;
-    char* ws_arc = ws + (size_t)passes * core_stride;
+    char* ws_arc = ws + (V_core > 0 ? core_workspace_bytes(M, d, V_core, k) : 0);
+    GemmPlan gp;
+    if (gemm_core) {
+        gp = make_gemm_plan(M, V_core, k);
+        hipError_t e = launch_gemm_partials(h, M, d, W_core, ids_core, V_core, k, ws + gp.keys_off,
+                                            ws + gp.stats_off, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
     // k may exceed one of the two parts; each part's slabs then simply hold fewer candidates
     const int k_core = k, k_arc = k;
 
@@ -222,14 +251,16 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
         const int m_end = row_off[s + 1];
         while (m0 < m_end) {
             const int pass = m0 / kMTile;
-            const int pass_end = (pass + 1) * kMTile;
+            const int pass_end = gemm_core ? m0 + kMTile : (pass + 1) * kMTile;
             const int rows = (m_end < pass_end ? m_end : pass_end) - m0;
             MergeSet core{}, arc{};
-            if (V_core > 0) {
+            if (gemm_core) {
+                core = MergeSet{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, m0, M};
+            } else if (V_core > 0) {
                 const int pass_rows = (M - pass * kMTile) < kMTile ? (M - pass * kMTile) : kMTile;
                 const Plan pc = make_plan(pass_rows, V_core, k_core, num_cu);
                 const char* w = ws + (size_t)pass * core_stride;
-                core = MergeSet{w + pc.keys_off, w + pc.stats_off, pc.n_slabs, m0 - pass * kMTile};
+                core = MergeSet{w + pc.keys_off, w + pc.stats_off, pc.n_slabs, m0 - pass * kMTile, kMTile};
             }
             if (V_arc > 0) {
                 const Plan pa = make_plan(rows, V_arc, k_arc, num_cu);
@@ -237,7 +268,7 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
                 hipError_t e = launch_partials(pa, hp + (size_t)m0 * d, rows, d, Wa, ids_arc + (size_t)s * V_arc,
                                                V_arc, k, ws_arc + pa.keys_off, ws_arc + pa.stats_off, st);
                 if (e != hipSuccess) return hip_fail(e);
-                arc = MergeSet{ws_arc + pa.keys_off, ws_arc + pa.stats_off, pa.n_slabs, 0};
+                arc = MergeSet{ws_arc + pa.keys_off, ws_arc + pa.stats_off, pa.n_slabs, 0, kMTile};
             }
             hipError_t e = launch_merge(core, arc, k, out_vals, out_ids, out_logz, m0, rows, st);
             if (e != hipSuccess) return hip_fail(e);

@@ -11,37 +11,10 @@
 
 #include <type_traits>
 
+#include "common.hpp"
 #include "plan.hpp"
 
 namespace evospec {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned long long u64;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef const u32x4 __attribute__((address_space(1))) * gvec_ptr;   // 16-byte loads from HBM
-
-// ---------------------------------------------------------------------------------------
-// (logit, id) -> one 64-bit key whose unsigned order is "larger logit first, then smaller
-// full-vocabulary id".  Key 0 is reserved for "no candidate".
-__device__ __forceinline__ uint32_t f32_to_ordered(float f) {
-    const uint32_t u = __float_as_uint(f + 0.0f);       // -0 -> +0 so that the two tie
-    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);   // negative: flip all bits, else the sign
-}
-__device__ __forceinline__ float ordered_to_f32(uint32_t o) {
-    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
-}
-__device__ __forceinline__ u64 make_key(float z, int32_t id) {
-    return ((u64)f32_to_ordered(z) << 32) | (uint32_t)(~(uint32_t)id);
-}
-__device__ __forceinline__ float key_value(u64 key) { return ordered_to_f32((uint32_t)(key >> 32)); }
-__device__ __forceinline__ int32_t key_id(u64 key) { return (int32_t)(~(uint32_t)key); }
-
-// Workgroup barrier that waits for this wave's LDS traffic only: global loads issued for
-// the next chunk stay in flight across it (a plain __syncthreads() would drain them).
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 // ---------------------------------------------------------------------------------------
 // Row insertion  W_act[slot] <- W_lm[id], act_ids[slot] <- id  (bit copy, 16 B per lane).
@@ -429,13 +402,6 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
 // batched variant).  Every slab's list is sorted, so its head is its maximum: per block of 256
 // lists the k-th largest head (together with the running result) bounds the answer from below,
 // at most k lists reach above that bound, and only their entries are ranked exactly.
-struct PartialSet {
-    const u64* keys;        // [n_slabs][64][k]
-    const float2* stats;    // [n_slabs][64]
-    int n_slabs;
-    int row_base;           // slot of this launch's block 0 inside the set's 64-row pass
-};
-
 constexpr int kMergeThreads = 256;
 
 __device__ __forceinline__ u64 wave_bcast(u64 x, int src_lane /*uniform*/) {
@@ -465,8 +431,8 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
     const int total = A.n_slabs + B.n_slabs;
 
     auto list_of = [&](int L) -> const u64* {
-        return L < A.n_slabs ? A.keys + ((size_t)L * kMTile + slotA) * k
-                             : B.keys + ((size_t)(L - A.n_slabs) * kMTile + slotB) * k;
+        return L < A.n_slabs ? A.keys + ((size_t)L * A.row_stride + slotA) * k
+                             : B.keys + ((size_t)(L - A.n_slabs) * B.row_stride + slotB) * k;
     };
     // the first block's list heads are fetched together with the statistics (one memory round trip)
     const u64 head_first = tid < total ? list_of(tid)[0] : 0;
@@ -474,8 +440,8 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
     // ---- log-normaliser: online (max, scaled sum) per thread, fixed-shape reduction
     float mx = -INFINITY, sm = 0.f;
     for (int t = tid; t < total; t += NT) {
-        const float2 st = t < A.n_slabs ? A.stats[(size_t)t * kMTile + slotA]
-                                        : B.stats[(size_t)(t - A.n_slabs) * kMTile + slotB];
+        const float2 st = t < A.n_slabs ? A.stats[(size_t)t * A.row_stride + slotA]
+                                        : B.stats[(size_t)(t - A.n_slabs) * B.row_stride + slotB];
         const float nm = fmaxf(mx, st.x);
         sm = (mx == -INFINITY ? 0.f : sm * __expf(mx - nm)) + st.y * __expf(st.x - nm);
         mx = nm;
@@ -622,8 +588,8 @@ hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const 
 
 hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
                         float* out_logz, int out_row0, int nrows, hipStream_t stream) {
-    PartialSet A{static_cast<const u64*>(a.keys), static_cast<const float2*>(a.stats), a.n_slabs, a.row_base};
-    PartialSet B{static_cast<const u64*>(b.keys), static_cast<const float2*>(b.stats), b.n_slabs, b.row_base};
+    PartialSet A{static_cast<const u64*>(a.keys), static_cast<const float2*>(a.stats), a.n_slabs, a.row_base, a.row_stride};
+    PartialSet B{static_cast<const u64*>(b.keys), static_cast<const float2*>(b.stats), b.n_slabs, b.row_base, b.row_stride};
     hipLaunchKernelGGL(lmhead_merge_kernel, dim3(nrows), dim3(kMergeThreads), 0, stream, A, B, k,
                        out_vals, out_ids, out_logz, out_row0);
     return hipGetLastError();

@@ -9,15 +9,19 @@ namespace evospec {
 
 // One set of slab partials as the merge kernel sees it.
 struct MergeSet {
-    const void* keys = nullptr;     // u64 [n_slabs][64][k]
-    const void* stats = nullptr;    // float2 [n_slabs][64]
+    const void* keys = nullptr;     // u64 [n_slabs][row_stride][k]
+    const void* stats = nullptr;    // float2 [n_slabs][row_stride]
     int n_slabs = 0;
-    int row_base = 0;               // slot (0..63) of the launch's first row inside the set
+    int row_base = 0;               // slot of the launch's first row inside the set
+    int row_stride = 64;            // draft-row slots per slab in the layout
 };
 
 hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
                            const int32_t* ids, int V_act, int k, void* keys, void* stats,
                            hipStream_t stream);
+// Large-M path: partials of all M draft rows, keys u64 [ceil(V_act/128)][M][k], stats float2 [..][M].
+hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, const int32_t* ids, int V_act,
+                                int k, void* keys, void* stats, hipStream_t stream);
 hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
                         float* out_logz, int out_row0, int nrows, hipStream_t stream);
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,

@@ -96,6 +96,27 @@ inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, in
     return best;
 }
 
+// Large-M path: 256 x 256 tiles, one partial per 128 active rows and draft row, all M rows in
+// one launch.  Taken from kGemmMinRows draft rows on, where the contraction, not the stream of
+// W_act, bounds the head.
+constexpr int kGemmTile = 256;
+constexpr int kGemmSlab = 128;
+constexpr int kGemmMinRows = 129;
+constexpr int kGemmKChunk = 32;       // the large-M kernel needs d to be a multiple of this
+inline bool use_gemm(int M, int d) { return M >= kGemmMinRows && d % kGemmKChunk == 0; }
+
+struct GemmPlan {
+    int n_slabs = 0;
+    size_t keys_off = 0, stats_off = 0, total_bytes = 0;
+};
+inline GemmPlan make_gemm_plan(int M, int V_act, int k) {
+    GemmPlan g;
+    g.n_slabs = (V_act + kGemmSlab - 1) / kGemmSlab;
+    g.stats_off = align_up((size_t)g.n_slabs * M * k * 8, 256);
+    g.total_bytes = g.stats_off + align_up((size_t)g.n_slabs * M * 8, 256);
+    return g;
+}
+
 // Upper bound of Plan::total_bytes over every slab shape (independent of the device).
 inline size_t workspace_upper_bound(int V_act, int k) {
     const size_t n_slabs = ((size_t)V_act + kRowsMinSlab - 1) / kRowsMinSlab;

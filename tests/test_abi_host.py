@@ -46,9 +46,15 @@ def test_workspace_bytes(ev):
     b = ev.workspace_bytes(60, 151936, 4096, 10)
     assert 0 < a < b
     assert ev.workspace_bytes(60, 36864, 4096, 20) > a
-    assert ev.workspace_bytes(960, 36864, 4096, 10) == a           # passes reuse the scratch
+    assert ev.workspace_bytes(128, 36864, 4096, 10) == a           # 64-row passes reuse the scratch
+    assert ev.workspace_bytes(960, 36864, 4104, 10) == a           # hidden size not a multiple of 32: passes
+    # from 129 rows on one launch keeps a partial per 128 active rows and draft row
+    big = ev.workspace_bytes(960, 36864, 4096, 10)
+    assert big >= 288 * 960 * (10 * 8 + 8)
     seg = ev.workspace_bytes_segmented(960, 32768, 2048, 16, 4096, 10)
-    assert seg >= 15 * ev.workspace_bytes(64, 32768, 4096, 10)
+    assert seg >= 256 * 960 * (10 * 8 + 8) + ev.workspace_bytes(64, 2048, 4096, 10)
+    seg_small = ev.workspace_bytes_segmented(128, 32768, 2048, 4, 4096, 10)
+    assert seg_small >= 2 * ev.workspace_bytes(64, 32768, 4096, 10)
     out = ctypes.c_size_t(0)
     L = ev.lib
     assert L.evospec_workspace_bytes(1, 10, 64, 1, None) == 1
