@@ -53,6 +53,12 @@ size_t core_workspace_bytes(int M, int d, int V_core, int k) {
     return passes * evospec::workspace_upper_bound(V_core, k);
 }
 
+// Chunks (pieces of at most 64 rows of one sequence) whose extension partials one launch keeps.
+size_t arc_chunks(int M, int S) {
+    const size_t n = (size_t)S + (size_t)M / evospec::kMTile + 1;
+    return n < (size_t)evospec::kMaxChunks ? n : (size_t)evospec::kMaxChunks;
+}
+
 }  // namespace
 
 using namespace evospec;
@@ -97,7 +103,7 @@ int evospec_workspace_bytes_segmented(int M, int V_core, int V_arc, int S, int d
     // extension scratch is reused per chunk
     size_t total = 0;
     if (V_core > 0) total += core_workspace_bytes(M, d, V_core, k);
-    if (V_arc > 0) total += workspace_upper_bound(V_arc, k);
+    if (V_arc > 0) total += arc_chunks(M, S) * workspace_upper_bound(V_arc, k);
     *out_bytes = total > 0 ? total : 256;
     return EVOSPEC_OK;
 }
@@ -221,61 +227,75 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
     char* ws = static_cast<char*>(workspace);
     const uint16_t* hp = static_cast<const uint16_t*>(h);
     const bool gemm_core = V_core > 0 && use_gemm(M, d);
-    const int passes = gemm_core ? 0 : (M + kMTile - 1) / kMTile;
     const size_t core_stride = V_core > 0 ? workspace_upper_bound(V_core, k) : 0;
+    const size_t arc_stride = V_arc > 0 ? workspace_upper_bound(V_arc, k) : 0;
     char* ws_arc = ws + (V_core > 0 ? core_workspace_bytes(M, d, V_core, k) : 0);
-    GemmPlan gp;
+
+    // shared core: every draft row against W_core, partials kept for all rows.  The 64-row
+    // passes all use the plan of a full pass, so that one merge launch can address any of them.
+    MergeSet core{};
     if (gemm_core) {
-        gp = make_gemm_plan(M, V_core, k);
+        const GemmPlan gp = make_gemm_plan(M, V_core, k);
         hipError_t e = launch_gemm_partials(h, M, d, W_core, ids_core, V_core, k, ws + gp.keys_off,
                                             ws + gp.stats_off, st);
         if (e != hipSuccess) return hip_fail(e);
+        core = MergeSet{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M};
+    } else if (V_core > 0) {
+        const Plan pc = make_plan(kMTile, V_core, k, num_cu);
+        for (int m0 = 0, pss = 0; m0 < M; m0 += kMTile, ++pss) {
+            const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
+            char* w = ws + (size_t)pss * core_stride;
+            hipError_t e = launch_partials(pc, hp + (size_t)m0 * d, rows, d, W_core, ids_core, V_core, k,
+                                           w + pc.keys_off, w + pc.stats_off, st);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        core = MergeSet{ws + pc.keys_off, ws + pc.stats_off, pc.n_slabs, 0, kMTile};
     }
-    // k may exceed one of the two parts; each part's slabs then simply hold fewer candidates
-    const int k_core = k, k_arc = k;
 
-    // shared core: every 64-row pass of h against W_core, partials kept per pass
-    for (int pss = 0; pss < passes && V_core > 0; ++pss) {
-        const int m0 = pss * kMTile;
-        const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
-        const Plan p = make_plan(rows, V_core, k_core, num_cu);
-        char* w = ws + (size_t)pss * core_stride;
-        hipError_t e = launch_partials(p, hp + (size_t)m0 * d, rows, d, W_core, ids_core, V_core, k,
-                                       w + p.keys_off, w + p.stats_off, st);
+    // per sequence: its rows against its own extension, then the merge of both partial sets,
+    // kMaxChunks chunks per launch.  A chunk has at most 64 rows and, with 64-row core passes,
+    // never crosses a pass boundary, so its core partials sit in one pass.
+    ChunkBatch cb;
+    cb.n = 0;
+    auto flush = [&]() -> int {
+        if (cb.n == 0) return EVOSPEC_OK;
+        int max_rows = 0;
+        for (int i = 0; i < cb.n; ++i) max_rows = cb.rows[i] > max_rows ? cb.rows[i] : max_rows;
+        MergeSet arc{};
+        if (V_arc > 0) {
+            const Plan pa = make_plan(max_rows, V_arc, k, num_cu, cb.n);
+            BatchLayout bl;
+            bl.seq_rows = V_arc;
+            bl.chunk_bytes = arc_stride;
+            hipError_t e = launch_partials_batch(pa, h, cb, bl, d, W_arc, ids_arc, V_arc, k,
+                                                 ws_arc + pa.keys_off, ws_arc + pa.stats_off, st);
+            if (e != hipSuccess) return hip_fail(e);
+            arc = MergeSet{ws_arc + pa.keys_off, ws_arc + pa.stats_off, pa.n_slabs, 0, kMTile};
+        }
+        hipError_t e = launch_merge_batch(core, core_stride, arc, arc_stride, cb, k, out_vals, out_ids, out_logz, st);
         if (e != hipSuccess) return hip_fail(e);
-    }
-    // per sequence: its rows against its own extension, then the merge of both partial sets.
-    // A chunk never crosses a 64-row pass boundary, so its core partials sit in one pass.
+        cb.n = 0;
+        return EVOSPEC_OK;
+    };
     for (int s = 0; s < S; ++s) {
         int m0 = row_off[s];
         const int m_end = row_off[s + 1];
         while (m0 < m_end) {
             const int pass = m0 / kMTile;
-            const int pass_end = gemm_core ? m0 + kMTile : (pass + 1) * kMTile;
-            const int rows = (m_end < pass_end ? m_end : pass_end) - m0;
-            MergeSet core{}, arc{};
-            if (gemm_core) {
-                core = MergeSet{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, m0, M};
-            } else if (V_core > 0) {
-                const int pass_rows = (M - pass * kMTile) < kMTile ? (M - pass * kMTile) : kMTile;
-                const Plan pc = make_plan(pass_rows, V_core, k_core, num_cu);
-                const char* w = ws + (size_t)pass * core_stride;
-                core = MergeSet{w + pc.keys_off, w + pc.stats_off, pc.n_slabs, m0 - pass * kMTile, kMTile};
+            const int piece_end = gemm_core ? m0 + kMTile : (pass + 1) * kMTile;
+            const int rows = (m_end < piece_end ? m_end : piece_end) - m0;
+            const int i = cb.n++;
+            cb.m0[i] = m0; cb.rows[i] = rows; cb.seq[i] = s;
+            cb.a_pass[i] = gemm_core ? 0 : pass;
+            cb.a_slot[i] = gemm_core ? m0 : m0 - pass * kMTile;
+            if (cb.n == kMaxChunks) {
+                const int rc2 = flush();
+                if (rc2) return rc2;
             }
-            if (V_arc > 0) {
-                const Plan pa = make_plan(rows, V_arc, k_arc, num_cu);
-                const uint16_t* Wa = static_cast<const uint16_t*>(W_arc) + (size_t)s * V_arc * d;
-                hipError_t e = launch_partials(pa, hp + (size_t)m0 * d, rows, d, Wa, ids_arc + (size_t)s * V_arc,
-                                               V_arc, k, ws_arc + pa.keys_off, ws_arc + pa.stats_off, st);
-                if (e != hipSuccess) return hip_fail(e);
-                arc = MergeSet{ws_arc + pa.keys_off, ws_arc + pa.stats_off, pa.n_slabs, 0, kMTile};
-            }
-            hipError_t e = launch_merge(core, arc, k, out_vals, out_ids, out_logz, m0, rows, st);
-            if (e != hipSuccess) return hip_fail(e);
             m0 += rows;
         }
     }
-    return EVOSPEC_OK;
+    return flush();
 }
 
 int evospec_validate_ids(const int32_t* ids, int n, int V, void* stream) {

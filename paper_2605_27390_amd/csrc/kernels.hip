@@ -79,10 +79,21 @@ validate_ids_kernel(const int32_t* __restrict__ ids, int n, int V, int* flag) {
 // Logits never leave the CU.
 template <int NW, int RGW, int RC, int MB, bool FULLK>
 __global__ void __launch_bounds__(NW * 64)
-lmhead_partials_kernel(const uint16_t* __restrict__ h, int rows, int d,
-                       const uint16_t* __restrict__ W, const int32_t* __restrict__ ids,
+lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int seq_rows,
+                       size_t chunk_keys, size_t chunk_stats, int d,
+                       const uint16_t* __restrict__ W_all, const int32_t* __restrict__ ids_all,
                        int V_act, int k, int GL,
-                       u64* __restrict__ part_keys, float2* __restrict__ part_stats) {
+                       u64* __restrict__ keys_all, float2* __restrict__ stats_all) {
+    // this workgroup's problem: chunk blockIdx.y of the batch (its draft rows, its sequence's
+    // rows of a per-sequence matrix, its own piece of the partials)
+    const int ci = blockIdx.y;
+    const int rows = cb.rows[ci];
+    const size_t seq_row0 = (size_t)cb.seq[ci] * seq_rows;
+    const uint16_t* __restrict__ h = h_all + (size_t)cb.m0[ci] * d;
+    const uint16_t* __restrict__ W = W_all + seq_row0 * d;
+    const int32_t* __restrict__ ids = ids_all ? ids_all + seq_row0 : nullptr;
+    u64* __restrict__ part_keys = keys_all + (size_t)ci * chunk_keys;
+    float2* __restrict__ part_stats = stats_all + (size_t)ci * chunk_stats;
     constexpr int NT = NW * 64;
     constexpr int RT = 16 * NW * RGW;
     constexpr int MR = 16 * MB;
@@ -411,9 +422,10 @@ __device__ __forceinline__ u64 wave_bcast(u64 x, int src_lane /*uniform*/) {
 }
 
 __global__ void __launch_bounds__(kMergeThreads)
-lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
+lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_keys, size_t a_pass_stats,
+                    size_t b_chunk_keys, size_t b_chunk_stats, int k,
                     float* __restrict__ out_vals, int32_t* __restrict__ out_ids,
-                    float* __restrict__ out_logz, int out_row0) {
+                    float* __restrict__ out_logz) {
     constexpr int NT = kMergeThreads;
     constexpr int NWV = NT / 64;
     __shared__ u64 run[2][kKMax];                    // running k best, descending
@@ -426,8 +438,15 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, int k,
     __shared__ float wave_m[NWV], wave_s[NWV];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int out_row = out_row0 + blockIdx.x;
-    const int slotA = A.row_base + blockIdx.x, slotB = B.row_base + blockIdx.x;
+    // row blockIdx.x of chunk blockIdx.y: where its partials sit in the two sets
+    const int chunk = blockIdx.y;
+    if ((int)blockIdx.x >= cb.rows[chunk]) return;                 // uniform: the grid spans the longest chunk
+    const int out_row = cb.m0[chunk] + blockIdx.x;
+    A.keys += (size_t)cb.a_pass[chunk] * a_pass_keys;
+    A.stats += (size_t)cb.a_pass[chunk] * a_pass_stats;
+    B.keys += (size_t)chunk * b_chunk_keys;
+    B.stats += (size_t)chunk * b_chunk_stats;
+    const int slotA = A.row_base + cb.a_slot[chunk] + blockIdx.x, slotB = B.row_base + blockIdx.x;
     const int total = A.n_slabs + B.n_slabs;
 
     auto list_of = [&](int L) -> const u64* {
@@ -540,8 +559,8 @@ namespace {
 constexpr int kMaxDevices = 64;
 
 template <int NW, int RGW, int RC, int MB, bool FULLK>
-hipError_t launch_partials_k(const Plan& p, const void* h, int rows, int d, const void* W,
-                             const int32_t* ids, int V_act, int k, void* keys, void* stats,
+hipError_t launch_partials_k(const Plan& p, const void* h, const ChunkBatch& cb, const BatchLayout& bl, int d,
+                             const void* W, const int32_t* ids, int V_act, int k, void* keys, void* stats,
                              hipStream_t stream) {
     auto kern = lmhead_partials_kernel<NW, RGW, RC, MB, FULLK>;
     static bool attr_set[kMaxDevices] = {};
@@ -554,45 +573,68 @@ hipError_t launch_partials_k(const Plan& p, const void* h, int rows, int d, cons
         if (e != hipSuccess) return e;
         if (dev >= 0 && dev < kMaxDevices) attr_set[dev] = true;
     }
-    hipLaunchKernelGGL(kern, dim3(p.n_slabs), dim3(NW * 64), p.lds_bytes, stream,
-                       static_cast<const uint16_t*>(h), rows, d, static_cast<const uint16_t*>(W), ids,
+    hipLaunchKernelGGL(kern, dim3(p.n_slabs, cb.n), dim3(NW * 64), p.lds_bytes, stream,
+                       static_cast<const uint16_t*>(h), cb, bl.seq_rows, bl.chunk_bytes / 8, bl.chunk_bytes / 8, d,
+                       static_cast<const uint16_t*>(W), ids,
                        V_act, k, p.gl, static_cast<u64*>(keys), static_cast<float2*>(stats));
     return hipGetLastError();
 }
 
 template <int NW, int RGW, int RC>
-hipError_t launch_partials_shape(const Plan& p, const void* h, int rows, int d, const void* W,
-                                 const int32_t* ids, int V_act, int k, void* keys, void* stats,
+hipError_t launch_partials_shape(const Plan& p, const void* h, const ChunkBatch& cb, const BatchLayout& bl, int d,
+                                 const void* W, const int32_t* ids, int V_act, int k, void* keys, void* stats,
                                  hipStream_t stream) {
     const bool full = d % kKC == 0;
 #define EVOSPEC_MB(MB_)                                                                              \
     if (p.mb == MB_)                                                                                 \
-        return full ? launch_partials_k<NW, RGW, RC, MB_, true>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream)   \
-                    : launch_partials_k<NW, RGW, RC, MB_, false>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
+        return full ? launch_partials_k<NW, RGW, RC, MB_, true>(p, h, cb, bl, d, W, ids, V_act, k, keys, stats, stream)   \
+                    : launch_partials_k<NW, RGW, RC, MB_, false>(p, h, cb, bl, d, W, ids, V_act, k, keys, stats, stream);
     EVOSPEC_MB(1) EVOSPEC_MB(2) EVOSPEC_MB(4)
 #undef EVOSPEC_MB
     return hipErrorInvalidValue;
 }
 }  // namespace
 
-hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
-                           const int32_t* ids, int V_act, int k, void* keys, void* stats,
-                           hipStream_t stream) {
+hipError_t launch_partials_batch(const Plan& p, const void* h, const ChunkBatch& cb, const BatchLayout& bl,
+                                 int d, const void* W, const int32_t* ids, int V_act, int k, void* keys,
+                                 void* stats, hipStream_t stream) {
+    if (cb.n < 1 || cb.n > kMaxChunks || bl.chunk_bytes % 8 != 0) return hipErrorInvalidValue;
 #define EVOSPEC_SHAPE(NW_, RGW_, RC_)                                                          \
     if (p.nw == NW_ && p.rgw == RGW_ && p.rc == RC_)                                           \
-        return launch_partials_shape<NW_, RGW_, RC_>(p, h, rows, d, W, ids, V_act, k, keys, stats, stream);
+        return launch_partials_shape<NW_, RGW_, RC_>(p, h, cb, bl, d, W, ids, V_act, k, keys, stats, stream);
     EVOSPEC_SLAB_SHAPES(EVOSPEC_SHAPE)
 #undef EVOSPEC_SHAPE
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
-                        float* out_logz, int out_row0, int nrows, hipStream_t stream) {
+hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
+                           const int32_t* ids, int V_act, int k, void* keys, void* stats,
+                           hipStream_t stream) {
+    ChunkBatch cb;
+    cb.n = 1; cb.m0[0] = 0; cb.rows[0] = rows; cb.seq[0] = 0; cb.a_pass[0] = 0; cb.a_slot[0] = 0;
+    return launch_partials_batch(p, h, cb, BatchLayout{}, d, W, ids, V_act, k, keys, stats, stream);
+}
+
+hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const MergeSet& b, size_t b_chunk_bytes,
+                              const ChunkBatch& cb, int k, float* out_vals, int32_t* out_ids,
+                              float* out_logz, hipStream_t stream) {
+    if (cb.n < 1 || cb.n > kMaxChunks || a_pass_bytes % 8 != 0 || b_chunk_bytes % 8 != 0) return hipErrorInvalidValue;
+    int max_rows = 0;
+    for (int i = 0; i < cb.n; ++i) max_rows = cb.rows[i] > max_rows ? cb.rows[i] : max_rows;
+    if (max_rows == 0) return hipSuccess;
     PartialSet A{static_cast<const u64*>(a.keys), static_cast<const float2*>(a.stats), a.n_slabs, a.row_base, a.row_stride};
     PartialSet B{static_cast<const u64*>(b.keys), static_cast<const float2*>(b.stats), b.n_slabs, b.row_base, b.row_stride};
-    hipLaunchKernelGGL(lmhead_merge_kernel, dim3(nrows), dim3(kMergeThreads), 0, stream, A, B, k,
-                       out_vals, out_ids, out_logz, out_row0);
+    hipLaunchKernelGGL(lmhead_merge_kernel, dim3(max_rows, cb.n), dim3(kMergeThreads), 0, stream, A, B, cb,
+                       a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k,
+                       out_vals, out_ids, out_logz);
     return hipGetLastError();
+}
+
+hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
+                        float* out_logz, int out_row0, int nrows, hipStream_t stream) {
+    ChunkBatch cb;
+    cb.n = 1; cb.m0[0] = out_row0; cb.rows[0] = nrows; cb.seq[0] = 0; cb.a_pass[0] = 0; cb.a_slot[0] = 0;
+    return launch_merge_batch(a, 0, b, 0, cb, k, out_vals, out_ids, out_logz, stream);
 }
 
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,

@@ -16,6 +16,23 @@ struct MergeSet {
     int row_stride = 64;            // draft-row slots per slab in the layout
 };
 
+// Where the chunks of a batched launch find their operands and leave their partials: chunk i reads
+// the rows [seq[i] * seq_rows, +V_act) of the matrix and id list, and writes at byte offset
+// i * chunk_bytes (a multiple of 8) from `keys` and `stats`.
+struct BatchLayout {
+    int seq_rows = 0;
+    size_t chunk_bytes = 0;
+};
+
+hipError_t launch_partials_batch(const Plan& p, const void* h, const ChunkBatch& cb, const BatchLayout& bl,
+                                 int d, const void* W, const int32_t* ids, int V_act, int k, void* keys,
+                                 void* stats, hipStream_t stream);
+// One launch merges every chunk of the batch: row r of chunk i takes slot a_slot[i] + r of the first
+// set (moved by a_pass[i] * a_pass_bytes) and slot r of the second (moved by i * b_chunk_bytes), and
+// writes output row m0[i] + r.
+hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const MergeSet& b, size_t b_chunk_bytes,
+                              const ChunkBatch& cb, int k, float* out_vals, int32_t* out_ids,
+                              float* out_logz, hipStream_t stream);
 hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
                            const int32_t* ids, int V_act, int k, void* keys, void* stats,
                            hipStream_t stream);

@@ -30,6 +30,19 @@ constexpr SlabShape kShapes[] = {EVOSPEC_SLAB_SHAPES(EVOSPEC_SHAPE_ENTRY)};
 #undef EVOSPEC_SHAPE_ENTRY
 constexpr int kNumShapes = sizeof(kShapes) / sizeof(kShapes[0]);
 
+// A batch of independent problems handled by one launch (grid.y): chunk i is the draft rows
+// [m0, m0 + rows) of h against the rows of sequence `seq` of a per-sequence matrix.  For the
+// merge, a_pass / a_slot locate the chunk's rows inside the first partial set.
+constexpr int kMaxChunks = 64;
+struct ChunkBatch {
+    int n = 0;
+    int m0[kMaxChunks];
+    int rows[kMaxChunks];
+    int seq[kMaxChunks];
+    int a_pass[kMaxChunks];
+    int a_slot[kMaxChunks];
+};
+
 struct Plan {
     int nw = 0, rgw = 0;     // wavefronts per workgroup, 16-row groups per wavefront
     int rc = 0;              // chunks in the W-operand ring
@@ -72,7 +85,8 @@ inline size_t lds_bytes_for(int nw, int rgw, int mb) {
 
 // Slab shape for V_act rows on a device with `num_cu` compute units: fewest row-rounds
 // (ceil(slabs / CUs) * RT); ties go to the larger slab (fewer partials to merge).
-inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, int k, int num_cu) {
+inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, int k, int num_cu,
+                      int replicas = 1 /*chunks that share the launch*/) {
     Plan best;
     long best_cost = -1;
     const int mb = mb_for_rows(rows);
@@ -82,7 +96,7 @@ inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, in
         const int n_slabs = (V_act + rt - 1) / rt;
         const size_t lds = lds_bytes_for(nw, rgw, mb);
         if (lds > (size_t)kLdsLimit) continue;
-        const long rounds = (n_slabs + num_cu - 1) / num_cu;
+        const long rounds = ((long)n_slabs * replicas + num_cu - 1) / num_cu;
         const long cost = rounds * rt;
         if (best_cost < 0 || cost < best_cost || (cost == best_cost && rt > best.rt)) {
             best_cost = cost;
