@@ -35,11 +35,14 @@ __device__ __forceinline__ void lds_barrier() {
 
 // One set of per-slab partial results as the merge kernel reads it.
 struct PartialSet {
-    const u64* keys;        // [n_slabs][row_stride][k]
+    const u64* keys;        // [n_slabs][row_stride][list_len]
     const float2* stats;    // [n_slabs][row_stride]
     int n_slabs;
     int row_base;           // slot of this launch's block 0 inside the set's row dimension
     int row_stride;         // draft-row slots per slab in the layout
+    int list_len;           // key slots per list (>= k); empty slots hold 0
+    int sorted;             // lists hold keys, descending (slot 0 is the maximum); else (logit, id)
+                            // pairs in any order, all ones = empty
 };
 
 }  // namespace evospec

@@ -30,10 +30,13 @@ constexpr int kGOperandBytes = kGemmTile * kGK * 2;           // 16 KB: 256 rows
 constexpr int kGStageBytes = 2 * kGOperandBytes;              // W_act rows, then h rows
 constexpr size_t kGLds = (size_t)kGStages * kGStageBytes;     // 128 KB
 constexpr int kGLoads = kGemmTile / 16 / 4;                   // direct-to-LDS loads per wavefront, operand and chunk
-constexpr int kGEpiBytes = 16 * kGemmSlab * 8 + kGemmSlab * 4;   // per wavefront: key lists, ids
+constexpr int kGFastLen = 16;                 // list length the staged common path of the epilogue handles
+constexpr int kGEpiBytes = 16 * kGemmSlab * 8 + 64 * 32 * 4 + kGemmSlab * 4;   // per wavefront: lists, parked logits, ids
+static_assert(8 * 16 * kGFastLen * 8 + 64 * 8 <= 16 * kGemmSlab * 8 + 64 * 32 * 4, "staged lists and spare slots fit");
+constexpr size_t kGLdsTotal = kGLds > 4ull * kGEpiBytes ? kGLds : 4ull * kGEpiBytes;
 
 static_assert(kGLds <= (size_t)kLdsLimit, "operand ring exceeds the LDS of a compute unit");
-static_assert(4 * kGEpiBytes <= (int)kGLds, "epilogue lists alias the operand ring");
+static_assert(kGLdsTotal <= (size_t)kLdsLimit, "epilogue lists exceed the LDS of a compute unit");
 static_assert(kGLoads == 4, "four wavefronts share 16 blocks of 16 rows");
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -54,15 +57,72 @@ __device__ __forceinline__ void mfma_acc(f32x4& c, const bf16x8& a, const bf16x8
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
+// The 4 lanes n16, n16+16, n16+32, n16+48 (one per 16-lane row of the wavefront) hold the four
+// quarters of a draft row's logits.  v_permlane16_swap exchanges the odd rows of its first operand
+// with the even rows of the second, v_permlane32_swap the upper half of the first with the lower
+// half of the second: applied to two copies of x they hand every lane both members of its pair of
+// rows, then of its pair of halves.
+// Eight independent values at a time, stage by stage (the scheduler is fenced in between).
+__device__ __forceinline__ void quad_max8(float (&x)[8]) {
+    float y[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x[i]), __float_as_uint(x[i]), false, false);
+        x[i] = __uint_as_float(a[0]); y[i] = __uint_as_float(a[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = fmaxf(x[i], y[i]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[i]), __float_as_uint(x[i]), false, false);
+        x[i] = __uint_as_float(b[0]); y[i] = __uint_as_float(b[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = fmaxf(x[i], y[i]);
+    __builtin_amdgcn_sched_barrier(0);
+}
+__device__ __forceinline__ void quad_sum8(float (&x)[8]) {
+    float y[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x[i]), __float_as_uint(x[i]), false, false);
+        x[i] = __uint_as_float(a[0]); y[i] = __uint_as_float(a[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] += y[i];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x[i]), __float_as_uint(x[i]), false, false);
+        x[i] = __uint_as_float(b[0]); y[i] = __uint_as_float(b[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] += y[i];
+    __builtin_amdgcn_sched_barrier(0);
+}
+// q[r] = x of the lane in row r (lane n16 + 16 r)
+__device__ __forceinline__ void quad_all(uint32_t x, uint32_t (&q)[4]) {
+    const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);      // a[0]: rows {0,0,2,2}, a[1]: rows {1,1,3,3}
+    const auto e = __builtin_amdgcn_permlane32_swap(a[0], a[0], false, false);  // e[0]: row 0 everywhere, e[1]: row 2
+    const auto o = __builtin_amdgcn_permlane32_swap(a[1], a[1], false, false);  // o[0]: row 1 everywhere, o[1]: row 3
+    q[0] = e[0]; q[1] = o[0]; q[2] = e[1]; q[3] = o[1];
+}
+
 }  // namespace
 
 __global__ void __launch_bounds__(256, 1)
 lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
-                   const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, int V_act, int k,
+                   const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, int V_act, int k, int list_len,
                    int m_tiles, u64* __restrict__ part_keys, float2* __restrict__ part_stats) {
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: keeps LDS destinations scalar
     const int n16 = lane & 15, g = lane >> 4;
     const int wv = w >> 1, wm = w & 1;                             // quadrant: active-row half, draft-row half
 
@@ -168,8 +228,12 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
     if (nvalid <= 0) return;                                       // quadrant wholly past the active set
     const int slab = tile_v * (kGemmTile / kGemmSlab) + wv;
     unsigned char* my = smem + (size_t)w * kGEpiBytes;
-    u64* list = reinterpret_cast<u64*>(my);                        // [16][128] surviving keys per draft row
-    int32_t* Ids = reinterpret_cast<int32_t*>(my + 16 * kGemmSlab * 8);   // [128]
+    // common path: [8][16][16] staged lists of all blocks, then one spare slot per lane;
+    // rare path (afterwards, same bytes): [16][128] full lists of one block, then [64][32] parked logits
+    u64* flist = reinterpret_cast<u64*>(my);
+    u64* list = reinterpret_cast<u64*>(my);
+    float* zpark = reinterpret_cast<float*>(my + 16 * kGemmSlab * 8);
+    int32_t* Ids = reinterpret_cast<int32_t*>(my + kGEpiBytes - kGemmSlab * 4);   // [128]
 
 #pragma unroll
     for (int i = 0; i < kGemmSlab / 64; ++i) {
@@ -178,87 +242,246 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     // lane's entries: active row (within the quadrant) 16 rg + 4 g + j  <->  bit 4 rg + j
-    int32_t idv[32];
     uint32_t vmask = 0;
+#pragma unroll
+    for (int rg = 0; rg < 8; ++rg)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (rg * 16 + 4 * g + j < nvalid) vmask |= 1u << (4 * rg + j);
+    if (nvalid < kGemmSlab) {                                      // ragged last slab: rows past the end never win
+#pragma unroll
+        for (int rg = 0; rg < 8; ++rg)
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (!((vmask >> (4 * rg + j)) & 1u)) acc[rg][mb][j] = -INFINITY;
+    }
+
+    // A wavefront runs alone on its SIMD here, so nothing hides a latency but its own independent
+    // work: every phase below runs over all 8 blocks of 16 draft rows before the next one starts.
+    // Lane (n16, g) holds, for draft row n16 of block mb, the 32 logits acc[0..7][mb][0..3]; the
+    // row's 128 logits are spread over the 4 lanes g = 0..3, which exchange values with the
+    // row-swap instructions (no LDS round trip).
+
+    // (an empty statement that "rewrites" the accumulators where they sit: copies read into
+    // ordinary registers by one phase are dropped instead of being carried, and spilled, to the next)
+    auto repin = [&]() {
+#pragma unroll
+        for (int rg = 0; rg < 8; ++rg)
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb) asm volatile("" : "+a"(acc[rg][mb]));
+    };
+    repin();
+    // Dependent vector instructions of one wavefront issue many cycles apart, so each phase is
+    // written as stages over the 8 independent blocks (8 instructions per stage) and the
+    // scheduler is fenced between stages so that it keeps them that way.
+#define EVOSPEC_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define EVOSPEC_MB(body) _Pragma("unroll") for (int mb = 0; mb < 8; ++mb) { body; } EVOSPEC_FENCE();
+
+    // -- phase 1: maxima of the 32 groups of 4 logits of every row, and the row maximum
+    float t[8][8], vm[8];
+#pragma unroll
+    for (int rg = 0; rg < 8; ++rg) {
+        float p0[8], p1[8];
+        EVOSPEC_MB(p0[mb] = fmaxf(acc[rg][mb][0], acc[rg][mb][1]))
+        EVOSPEC_MB(p1[mb] = fmaxf(acc[rg][mb][2], acc[rg][mb][3]))
+        EVOSPEC_MB(t[mb][rg] = fmaxf(p0[mb], p1[mb]))
+    }
+    {
+        float p0[8], p1[8], p2[8], p3[8];
+        EVOSPEC_MB(p0[mb] = fmaxf(t[mb][0], t[mb][1]))
+        EVOSPEC_MB(p1[mb] = fmaxf(t[mb][2], t[mb][3]))
+        EVOSPEC_MB(p2[mb] = fmaxf(t[mb][4], t[mb][5]))
+        EVOSPEC_MB(p3[mb] = fmaxf(t[mb][6], t[mb][7]))
+        EVOSPEC_MB(p0[mb] = fmaxf(p0[mb], p1[mb]))
+        EVOSPEC_MB(p2[mb] = fmaxf(p2[mb], p3[mb]))
+        EVOSPEC_MB(vm[mb] = fmaxf(p0[mb], p2[mb]))
+        quad_max8(vm);
+    }
+
+    // -- phase 2: lower bound of every row's k-th best logit.  Each lane sorts its 8 group maxima;
+    // k rounds then take the largest head of the row's 4 lanes and pop it wherever it is the head:
+    // at least k group maxima, hence k logits, reach the last value taken.  With more than 32
+    // wanted, or fewer groups than k, the bound stays at -inf and every valid entry is kept.
+    float tau[8];
+#pragma unroll
+    for (int mb = 0; mb < 8; ++mb) tau[mb] = -INFINITY;
+    if (k <= 32) {
+#define EVOSPEC_CE(I, J) { float hi[8]; EVOSPEC_MB(hi[mb] = fmaxf(t[mb][I], t[mb][J])) \
+                           EVOSPEC_MB(t[mb][J] = fminf(t[mb][I], t[mb][J])) EVOSPEC_MB(t[mb][I] = hi[mb]) }
+        EVOSPEC_CE(0, 1) EVOSPEC_CE(2, 3) EVOSPEC_CE(4, 5) EVOSPEC_CE(6, 7)
+        EVOSPEC_CE(0, 2) EVOSPEC_CE(1, 3) EVOSPEC_CE(4, 6) EVOSPEC_CE(5, 7)
+        EVOSPEC_CE(1, 2) EVOSPEC_CE(5, 6) EVOSPEC_CE(0, 4) EVOSPEC_CE(3, 7)
+        EVOSPEC_CE(1, 5) EVOSPEC_CE(2, 6)
+        EVOSPEC_CE(1, 4) EVOSPEC_CE(3, 6)
+        EVOSPEC_CE(2, 4) EVOSPEC_CE(3, 5)
+        EVOSPEC_CE(3, 4)
+#undef EVOSPEC_CE
+        for (int r = 0; r < k; ++r) {
+            EVOSPEC_MB(tau[mb] = t[mb][0])
+            quad_max8(tau);
+            // pop the head where it is the value just taken: all ones / zero select, no compare chain
+            uint32_t pop[8];
+            EVOSPEC_MB(pop[mb] = t[mb][0] == tau[mb] ? ~0u : 0u)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                EVOSPEC_MB(const uint32_t cur = __float_as_uint(t[mb][i]);
+                           const uint32_t nxt = i < 7 ? __float_as_uint(t[mb][i + 1]) : 0xff800000u;
+                           t[mb][i] = __uint_as_float((pop[mb] & nxt) | (~pop[mb] & cur)))
+            }
+        }
+    }
+
+    repin();
+    // -- phase 3: sum of exponentials, exp(z - vm) = 2^(z log2(e) - vm log2(e)), two running sums per block
+    uint32_t mask[8];
+    float se[8];
+    {
+        float nvm[8], s0[8], s1[8];
+        EVOSPEC_MB(nvm[mb] = -vm[mb] * 1.44269504f; s0[mb] = 0.f; s1[mb] = 0.f)
+#pragma unroll
+        for (int rg = 0; rg < 8; ++rg) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float x[8];
+                EVOSPEC_MB(x[mb] = __builtin_fmaf(acc[rg][mb][j], 1.44269504f, nvm[mb]))
+                EVOSPEC_MB(x[mb] = __builtin_amdgcn_exp2f(x[mb]))
+                if (j & 1) { EVOSPEC_MB(s1[mb] += x[mb]) } else { EVOSPEC_MB(s0[mb] += x[mb]) }
+            }
+        }
+        EVOSPEC_MB(se[mb] = s0[mb] + s1[mb])
+        quad_sum8(se);
+    }
+    repin();
+    // -- phase 3b: survivor masks without a compare per entry: the sign of (logit - bound) is
+    // shifted in, last entry first, so that entry i ends up as bit i ("below the bound")
+    {
+        uint32_t below[8];
+        EVOSPEC_MB(below[mb] = 0u)
+#pragma unroll
+        for (int i = 31; i >= 0; --i) {
+            float df[8];
+            EVOSPEC_MB(df[mb] = acc[i >> 2][mb][i & 3] - tau[mb])
+            EVOSPEC_MB(below[mb] = __builtin_amdgcn_alignbit(below[mb], __float_as_uint(df[mb]), 31))
+        }
+        EVOSPEC_MB(mask[mb] = ~below[mb] & vmask)
+    }
+    const int mrow0 = m0 + wm * 128 + n16;                         // draft row of block 0
+#pragma unroll
+    for (int mb = 0; mb < 8; ++mb)
+        if (g == 0 && mrow0 + 16 * mb < M) part_stats[(size_t)slab * M + mrow0 + 16 * mb] = make_float2(vm[mb], se[mb]);
+
+    // survivors per lane (<= 32), four blocks to a register; from the 4 lanes of a row: the offset
+    // of this lane's survivors in the row's list and the list length L (<= 128), still packed
+    uint32_t basep[2], Lp[2];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+        const uint32_t pk = __popc(mask[4 * hf]) | (__popc(mask[4 * hf + 1]) << 8) | (__popc(mask[4 * hf + 2]) << 16) |
+                            (__popc(mask[4 * hf + 3]) << 24);
+        uint32_t q[4];
+        quad_all(pk, q);
+        basep[hf] = (g > 0 ? q[0] : 0u) + (g > 1 ? q[1] : 0u) + (g > 2 ? q[2] : 0u);
+        Lp[hf] = q[0] + q[1] + q[2] + q[3];
+    }
+    // blocks in which every row's survivors fit a list go straight out (wave-uniform choice)
+    uint32_t fast = 0;
+#pragma unroll
+    for (int mb = 0; mb < 8; ++mb) {
+        const int L = (Lp[mb >> 2] >> (8 * (mb & 3))) & 0xff;
+        if (list_len == kGFastLen && __ballot(L > kGFastLen) == 0) fast |= 1u << mb;
+    }
+
+    repin();
+    int32_t idv[32];                                               // full-vocabulary ids of the lane's entries
 #pragma unroll
     for (int rg = 0; rg < 8; ++rg) {
         const int4 q = *reinterpret_cast<const int4*>(Ids + rg * 16 + 4 * g);
         idv[4 * rg + 0] = q.x; idv[4 * rg + 1] = q.y; idv[4 * rg + 2] = q.z; idv[4 * rg + 3] = q.w;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (rg * 16 + 4 * g + j < nvalid) vmask |= 1u << (4 * rg + j);
     }
-
+    // -- phase 4: the survivors of every row, as (logit, id) pairs in no particular order, are
+    // gathered into the row's 16-slot list in LDS (empty slots: all ones) and the lists copied to the
+    // workspace a full line at a time; the merge ranks.  No branch or compare per entry: an entry
+    // that is not a survivor goes to the lane's spare slot.
+    {
+        const u32x4 ones = {~0u, ~0u, ~0u, ~0u};
 #pragma unroll
-    for (int mb = 0; mb < 8; ++mb) {
-        const int m = m0 + wm * 128 + mb * 16 + n16;
-        const bool m_ok = m < M;
-        float v[32];
-#pragma unroll
-        for (int rg = 0; rg < 8; ++rg)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                v[4 * rg + j] = ((vmask >> (4 * rg + j)) & 1u) ? acc[rg][mb][j] : -INFINITY;
-
-        // statistics of the quadrant's 128 logits of draft row m (4 lanes x 32 entries)
-        float t[8];
-#pragma unroll
-        for (int rg = 0; rg < 8; ++rg)
-            t[rg] = fmaxf(fmaxf(v[4 * rg], v[4 * rg + 1]), fmaxf(v[4 * rg + 2], v[4 * rg + 3]));
-        float vmax = t[0];
-#pragma unroll
-        for (int rg = 1; rg < 8; ++rg) vmax = fmaxf(vmax, t[rg]);
-        vmax = fmaxf(vmax, __shfl_xor(vmax, 16));
-        vmax = fmaxf(vmax, __shfl_xor(vmax, 32));
-        float se = 0.f;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) se += __expf(v[i] - vmax);
-        se += __shfl_xor(se, 16);
-        se += __shfl_xor(se, 32);
-        const size_t slot = (size_t)slab * M + (m_ok ? m : 0);
-        if (g == 0 && m_ok) part_stats[slot] = make_float2(vmax, se);
-
-        // lower bound of the k-th best logit: the k-th largest distinct maximum of the 32 groups
-        // of 4 entries (k rounds of "take the maximum, strike it out"); with more than 32 wanted,
-        // or fewer distinct maxima than k, every valid entry is ranked
-        float tau = -INFINITY;
-        if (k <= 32) {
-            for (int r = 0; r < k; ++r) {
-                float lm = t[0];
-#pragma unroll
-                for (int rg = 1; rg < 8; ++rg) lm = fmaxf(lm, t[rg]);
-                lm = fmaxf(lm, __shfl_xor(lm, 16));
-                lm = fmaxf(lm, __shfl_xor(lm, 32));
-                tau = lm;
-#pragma unroll
-                for (int rg = 0; rg < 8; ++rg) t[rg] = t[rg] >= lm ? -INFINITY : t[rg];
-            }
-        }
-        uint32_t mask = 0;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) mask |= (v[i] >= tau ? 1u : 0u) << i;
-        mask &= vmask;
-        const int cnt = __popc(mask);
-        const int c0 = __shfl(cnt, n16), c1 = __shfl(cnt, n16 + 16), c2 = __shfl(cnt, n16 + 32),
-                  c3 = __shfl(cnt, n16 + 48);
-        const int base = (g > 0 ? c0 : 0) + (g > 1 ? c1 : 0) + (g > 2 ? c2 : 0);
-        const int L = c0 + c1 + c2 + c3;                           // <= 128
-        u64* mine = list + n16 * kGemmSlab;
-#pragma unroll
-        for (int i = 0; i < 32; ++i)
-            if ((mask >> i) & 1u) mine[base + __popc(mask & ((1u << i) - 1u))] = make_key(v[i], idv[i]);
+        for (int it = 0; it < 8 * 16 * kGFastLen * 8 / 1024; ++it)
+            *reinterpret_cast<u32x4*>(my + (it * 64 + lane) * 16) = ones;
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const uint32_t spare_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u64*)(flist + 8 * 16 * kGFastLen + lane);
+        uint32_t mk[8], rel[8];                                    // survivor mask; row list start - spare slot (bytes)
+#pragma unroll
+        for (int mb = 0; mb < 8; ++mb) {
+            const int base = (basep[mb >> 2] >> (8 * (mb & 3))) & 0xff;
+            mk[mb] = ((fast >> mb) & 1u) ? mask[mb] : 0u;
+            rel[mb] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) u64*)(flist + (mb * 16 + n16) * kGFastLen + base) - spare_a;
+        }
+        EVOSPEC_FENCE();
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            uint32_t at[8], sel[8];
+            EVOSPEC_MB(at[mb] = mk[mb] & ((1u << i) - 1u))
+            EVOSPEC_MB(at[mb] = __popc(at[mb]))
+            EVOSPEC_MB(sel[mb] = (uint32_t)__builtin_amdgcn_sbfe((int)mk[mb], i, 1))
+            EVOSPEC_MB(at[mb] = rel[mb] + 8u * at[mb])
+            EVOSPEC_MB(at[mb] &= sel[mb])
+            EVOSPEC_MB(at[mb] += spare_a)
+            EVOSPEC_MB(*(__attribute__((address_space(3))) u64*)(uintptr_t)at[mb] =
+                           ((u64)__float_as_uint(acc[i >> 2][mb][i & 3]) << 32) | (uint32_t)idv[i])
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        // piece p = 64 it + lane of the staged lists: block p / 128, row (p / 8) % 16, 16 bytes p % 8
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int mb = it >> 1, r16 = ((it & 1) << 3) | (lane >> 3);
+            const int m = m0 + wm * 128 + 16 * mb + r16;
+            const u32x4 q = *reinterpret_cast<const u32x4*>(my + (it * 64 + lane) * 16);
+            if (((fast >> mb) & 1u) && m < M)
+                *reinterpret_cast<u32x4*>(part_keys + ((size_t)slab * M + m) * kGFastLen + 2 * (lane & 7)) = q;
+        }
+    }
+#undef EVOSPEC_MB
+#undef EVOSPEC_FENCE
+    if (fast == 0xffu) return;
+    repin();
 
-        // exact rank of every survivor among the survivors of its draft row (keys are distinct)
-        u64* dst = part_keys + slot * k;
+    // -- rare path, block by block: a row with more survivors than a list holds (many equal logits,
+    // or k close to or above the number of groups).  The block's logits are parked in LDS so that
+    // one rolled copy of the code serves all blocks: keys of the survivors into per-row lists,
+    // exact rank among the row's survivors, the k best kept.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");            // the staged lists have been read
+    float* zbuf = zpark + lane * 32;
+    for (int mbr = 0; mbr < 8; ++mbr) {
+        if ((fast >> mbr) & 1u) continue;
+        uint32_t mk = 0;
+#pragma unroll
+        for (int mb = 0; mb < 8; ++mb) {
+            if (mb != mbr) continue;                               // uniform
+            mk = mask[mb];
+#pragma unroll
+            for (int rg = 0; rg < 8; ++rg) *reinterpret_cast<f32x4*>(zbuf + 4 * rg) = acc[rg][mb];
+        }
+        const int base = (basep[mbr >> 2] >> (8 * (mbr & 3))) & 0xff;
+        const int L = (Lp[mbr >> 2] >> (8 * (mbr & 3))) & 0xff;
+        const int m = mrow0 + 16 * mbr;
+        const bool m_ok = m < M;
+        u64* mine = list + n16 * kGemmSlab;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        int pos = base;
+        for (int i = 0; i < 32; ++i) {
+            if ((mk >> i) & 1u) mine[pos++] = make_key(zbuf[i], Ids[(i >> 2) * 16 + 4 * g + (i & 3)]);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        u64* dst = part_keys + ((size_t)slab * M + (m_ok ? m : 0)) * list_len;
         for (int e = g; e < L; e += 4) {
             const u64 key = mine[e];
             int rank = 0;
             for (int f = 0; f < L; ++f) rank += mine[f] > key ? 1 : 0;
-            if (rank < k && m_ok) dst[rank] = key;
+            if (rank < k && m_ok) dst[rank] = ((u64)__float_as_uint(key_value(key)) << 32) | (uint32_t)key_id(key);
         }
         if (m_ok)
-            for (int r = L + g; r < k; r += 4) dst[r] = 0;         // fewer than k rows in this slab
+            for (int r = (L < k ? L : k) + g; r < list_len; r += 4) dst[r] = ~0ull;
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
 }
@@ -276,12 +499,12 @@ hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, cons
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevices || !attr_set[dev]) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGLds);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGLdsTotal);
         if (e != hipSuccess) return e;
         if (dev >= 0 && dev < kMaxDevices) attr_set[dev] = true;
     }
-    hipLaunchKernelGGL(kern, dim3(v_tiles * m_tiles), dim3(256), kGLds, stream,
-                       static_cast<const uint16_t*>(h), M, d, static_cast<const uint16_t*>(W), ids, V_act, k,
+    hipLaunchKernelGGL(kern, dim3(v_tiles * m_tiles), dim3(256), kGLdsTotal, stream,
+                       static_cast<const uint16_t*>(h), M, d, static_cast<const uint16_t*>(W), ids, V_act, k, gemm_list_len(k),
                        m_tiles, static_cast<u64*>(keys), static_cast<float2*>(stats));
     return hipGetLastError();
 }

@@ -415,6 +415,11 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
 // at most k lists reach above that bound, and only their entries are ranked exactly.
 constexpr int kMergeThreads = 256;
 
+// An unranked list slot holds (logit bits << 32) | id; all ones = empty.
+__device__ __forceinline__ u64 pair_key(uint32_t zbits, uint32_t id) {
+    return id == 0xffffffffu ? 0ull : make_key(__uint_as_float(zbits), (int32_t)id);
+}
+
 __device__ __forceinline__ u64 wave_bcast(u64 x, int src_lane /*uniform*/) {
     const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)x, src_lane);
     const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), src_lane);
@@ -433,6 +438,7 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
     constexpr int kPendCap = kKMax * kKMax + kKMax;
     __shared__ u64 pend[kPendCap];                   // entries that reach the bound
     __shared__ const u64* qual[kKMax];             // lists whose head reaches the bound
+    __shared__ int qual_len[kKMax];
     __shared__ u64 tau_s;
     __shared__ int npend, nqual;
     __shared__ float wave_m[NWV], wave_s[NWV];
@@ -450,11 +456,29 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
     const int total = A.n_slabs + B.n_slabs;
 
     auto list_of = [&](int L) -> const u64* {
-        return L < A.n_slabs ? A.keys + ((size_t)L * A.row_stride + slotA) * k
-                             : B.keys + ((size_t)(L - A.n_slabs) * B.row_stride + slotB) * k;
+        return L < A.n_slabs ? A.keys + ((size_t)L * A.row_stride + slotA) * A.list_len
+                             : B.keys + ((size_t)(L - A.n_slabs) * B.row_stride + slotB) * B.list_len;
     };
+    auto len_of = [&](int L) { return L < A.n_slabs ? A.list_len : B.list_len; };
+    auto sorted_of = [&](int L) { return (L < A.n_slabs ? A.sorted : B.sorted) != 0; };
+    // a list's best key: its first slot if it is sorted, else the maximum over its slots (an even
+    // number of (logit, id) pairs, 16-byte aligned)
+    auto head_of = [&](int L) -> u64 {
+        const u64* p = list_of(L);
+        if (sorted_of(L)) return p[0];
+        u64 hd = 0;
+        const int n = len_of(L);
+        for (int j = 0; j < n; j += 2) {
+            const u32x4 q = *(gvec_ptr)(p + j);
+            const u64 k0 = pair_key(q[1], q[0]), k1 = pair_key(q[3], q[2]);
+            hd = k0 > hd ? k0 : hd;
+            hd = k1 > hd ? k1 : hd;
+        }
+        return hd;
+    };
+    const int max_len = A.list_len > B.list_len ? A.list_len : B.list_len;
     // the first block's list heads are fetched together with the statistics (one memory round trip)
-    const u64 head_first = tid < total ? list_of(tid)[0] : 0;
+    const u64 head_first = tid < total ? head_of(tid) : 0;
 
     // ---- log-normaliser: online (max, scaled sum) per thread, fixed-shape reduction
     float mx = -INFINITY, sm = 0.f;
@@ -491,7 +515,7 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
     for (int base = 0; base < total; base += NT) {
         const int L = base + tid;
         const u64* lst = L < total ? list_of(L) : nullptr;
-        u64 head = base == 0 ? head_first : (lst ? lst[0] : 0);
+        u64 head = base == 0 ? head_first : (lst ? head_of(L) : 0);
         if (head <= thr) head = 0;                   // cannot improve the running result
         // (1) rank of this list's head among the wave's 64 heads; the wave's k best go to cand
         int rank = 0;
@@ -515,13 +539,15 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
         //     qualifying lists are read by all threads at once (one entry per thread and round)
         const u64 t = tau_s;
         // (capacity checks only matter if the caller broke the unique-id precondition)
-        if (head != 0 && head >= t) { const int qi = atomicAdd(&nqual, 1); if (qi < kKMax) qual[qi] = lst; }
+        if (head != 0 && head >= t) { const int qi = atomicAdd(&nqual, 1); if (qi < kKMax) { qual[qi] = lst; qual_len[qi] = sorted_of(L) ? len_of(L) : -len_of(L); } }
         if (tid < nrun && run[cur][tid] >= t) pend[atomicAdd(&npend, 1)] = run[cur][tid];
         __syncthreads();
         const int nq = nqual < kKMax ? nqual : kKMax;
-        for (int e = tid; e < nq * k; e += NT) {
-            const int li = e / k, j = e - li * k;
-            const u64 key = qual[li][j];
+        for (int e = tid; e < nq * max_len; e += NT) {
+            const int li = e / max_len, j = e - li * max_len;
+            const int ql = qual_len[li];                // negative: (logit, id) pairs
+            u64 key = j < (ql < 0 ? -ql : ql) ? qual[li][j] : 0;
+            if (ql < 0) key = pair_key((uint32_t)(key >> 32), (uint32_t)key);
             if (key != 0 && key >= t) { const int pi = atomicAdd(&npend, 1); if (pi < kPendCap) pend[pi] = key; }
         }
         __syncthreads();
@@ -622,8 +648,13 @@ hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const Merg
     int max_rows = 0;
     for (int i = 0; i < cb.n; ++i) max_rows = cb.rows[i] > max_rows ? cb.rows[i] : max_rows;
     if (max_rows == 0) return hipSuccess;
-    PartialSet A{static_cast<const u64*>(a.keys), static_cast<const float2*>(a.stats), a.n_slabs, a.row_base, a.row_stride};
-    PartialSet B{static_cast<const u64*>(b.keys), static_cast<const float2*>(b.stats), b.n_slabs, b.row_base, b.row_stride};
+    if ((a.list_len != 0 && (a.list_len < k || a.list_len > kKMax || (a.list_len & 1))) ||
+        (b.list_len != 0 && (b.list_len < k || b.list_len > kKMax || (b.list_len & 1))))
+        return hipErrorInvalidValue;
+    PartialSet A{static_cast<const u64*>(a.keys), static_cast<const float2*>(a.stats), a.n_slabs, a.row_base, a.row_stride,
+                 a.list_len ? a.list_len : k, a.list_len == 0};
+    PartialSet B{static_cast<const u64*>(b.keys), static_cast<const float2*>(b.stats), b.n_slabs, b.row_base, b.row_stride,
+                 b.list_len ? b.list_len : k, b.list_len == 0};
     hipLaunchKernelGGL(lmhead_merge_kernel, dim3(max_rows, cb.n), dim3(kMergeThreads), 0, stream, A, B, cb,
                        a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k,
                        out_vals, out_ids, out_logz);

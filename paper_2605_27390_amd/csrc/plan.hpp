@@ -119,14 +119,20 @@ constexpr int kGemmMinRows = 129;
 constexpr int kGemmKChunk = 32;       // the large-M kernel needs d to be a multiple of this
 inline bool use_gemm(int M, int d) { return M >= kGemmMinRows && d % kGemmKChunk == 0; }
 
+// Key slots per (slab, draft row) list of the large-M path: the kernel leaves every logit that
+// reaches a lower bound of the slab's k-th best, unranked; rarely more than k + a few.
+inline int gemm_list_len(int k) { return k <= 16 ? 16 : (k <= 32 ? 32 : 64); }
+
 struct GemmPlan {
     int n_slabs = 0;
+    int list_len = 0;
     size_t keys_off = 0, stats_off = 0, total_bytes = 0;
 };
 inline GemmPlan make_gemm_plan(int M, int V_act, int k) {
     GemmPlan g;
     g.n_slabs = (V_act + kGemmSlab - 1) / kGemmSlab;
-    g.stats_off = align_up((size_t)g.n_slabs * M * k * 8, 256);
+    g.list_len = gemm_list_len(k);
+    g.stats_off = align_up((size_t)g.n_slabs * M * g.list_len * 8, 256);
     g.total_bytes = g.stats_off + align_up((size_t)g.n_slabs * M * 8, 256);
     return g;
 }
