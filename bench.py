@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=4, help="distinct W_act copies rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the head at the paper's own active-set sizes (adds extra.sweep)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU kernel path; --gpus must be 1 "
@@ -227,6 +229,38 @@ def main() -> int:
                                  "mfma_frac_bf16": round(flops / seg_us / 1e6 / 2500.0, 4),
                                  "rows_per_s": round(Mb / (seg_us * 1e-6), 1)}
         del W_core, W_arc, ws_b
+
+    if args.sweep and args.config == "draft60":
+        # the paper's own active-set sizes (Table 1 and the default setting), same rotation rule:
+        # enough copies of W_act that the weights come from HBM
+        sweep = []
+        W_by_shape = {(V, d): W_lm}
+        for name, d_s, V_s, nc, na, M_s, k_s in gi.SWEEP:
+            if (V_s, d_s) not in W_by_shape:
+                W_by_shape[(V_s, d_s)] = dev_bf16(gi.gen_W_lm(V_s, d_s, gi.SEED_W + 1))
+            Wl = W_by_shape[(V_s, d_s)]
+            core_s, arc_s = gi.core_arc_ids(V_s, nc, na, gi.SEED_IDS + 40)
+            ids_s = torch.from_numpy(np.concatenate([core_s, arc_s])).to(dev)
+            Va = nc + na
+            Rs = max(2, int(-(-4 * 256e6 // (Va * d_s * 2))))
+            Ws = [torch.empty((Va, d_s), dtype=torch.bfloat16, device=dev) for _ in range(Rs)]
+            Is = [torch.empty((Va,), dtype=torch.int32, device=dev) for _ in range(Rs)]
+            for r in range(Rs):
+                ev.active_gather(Wl, ids_s, None, Ws[r], Is[r])
+            h_s = dev_bf16(gi.gen_h(M_s, d_s, gi.SEED_H + 60))
+            ws_s = torch.empty(ev.workspace_bytes(M_s, Va, d_s, k_s), dtype=torch.uint8, device=dev)
+            ov_s = torch.empty((M_s, k_s), dtype=torch.float32, device=dev)
+            oi_s = torch.empty((M_s, k_s), dtype=torch.int32, device=dev)
+            ol_s = torch.empty((M_s,), dtype=torch.float32, device=dev)
+            us = timed(lambda i: ev.active_lmhead_topk(h_s, Ws[i % Rs], Is[i % Rs], k_s, ov_s, oi_s, ol_s, ws_s), 100)
+            ws_f = torch.empty(ev.workspace_bytes(M_s, V_s, d_s, k_s), dtype=torch.uint8, device=dev)
+            full = timed(lambda i: ev.active_lmhead_topk(h_s, Wl, None, k_s, ov_s, oi_s, ol_s, ws_f), 20, warm=3)
+            sweep.append({"name": name, "d": d_s, "V": V_s, "V_act": Va, "M": M_s, "copies": Rs,
+                          "head_us": round(us, 2),
+                          "hbm_gbps": round(algorithmic_bytes(Va, d_s, M_s, k_s) / us / 1e3, 1),
+                          "fullvocab_head_us": round(full, 2), "speedup_vs_fullvocab": round(full / us, 2)})
+            del Ws, Is, ws_s, ws_f
+        extra["sweep"] = sweep
 
     # ---------------------------------------------------------------- CPU oracle on the host cores
     cpu = None

@@ -38,6 +38,14 @@ CONFIGS = {
 }
 
 
+# Active-set sizes of the paper's own experiments (Table 1 sweeps |V_static| in {8k, 16k, 32k} and
+# N_dyn in {256, 512, 1024}; the default setting of the hyper-parameter table is 32,000 + 256) and
+# a second model shape (hidden size 2,048, vocabulary 128,256).  (name, d, V, n_core, n_arc, M, k)
+SWEEP = [("default_32000+256", 4096, 151936, 32000, 256, 60, 10)]
+SWEEP += [(f"{c // 1024}k+{a}", 4096, 151936, c, a, 60, 10) for c in (8192, 16384, 32768) for a in (256, 512, 1024)]
+SWEEP += [("d2048_32000+256", 2048, 128256, 32000, 256, 60, 10)]
+
+
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns (finite inputs)."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)

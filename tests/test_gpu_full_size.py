@@ -131,3 +131,24 @@ def test_batched_serving(ev, oracle_mod, lm_head):
         member = np.zeros(V, dtype=bool)
         member[union] = True
         assert member[i[row_off[s]:row_off[s + 1]]].all()
+
+
+@pytest.mark.parametrize("shape", [s for s in gi.SWEEP if s[1] == 4096 and s[0] in
+                                   ("default_32000+256", "8k+256", "16k+1024")], ids=lambda s: s[0])
+def test_paper_active_set_sizes(ev, oracle_mod, lm_head, shape):
+    """The active-set sizes of the paper's own experiments (Table 1 and the default setting):
+    gather + head against the oracle on every logit."""
+    import torch
+    W_bits, W_lm = lm_head
+    name, d, V, n_core, n_arc, M, k = shape
+    core, arc = gi.core_arc_ids(V, n_core, n_arc, gi.SEED_IDS + 40)
+    ids = np.concatenate([core, arc])
+    h = gi.gen_h(M, d, gi.SEED_H + 60)
+    W_act = torch.empty((ids.shape[0], d), dtype=torch.bfloat16, device="cuda")
+    act_ids = torch.empty((ids.shape[0],), dtype=torch.int32, device="cuda")
+    ev.active_gather(W_lm, to_dev_i32(ids), None, W_act, act_ids)
+    v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act, act_ids, k)
+    torch.cuda.synchronize()
+    assert np.array_equal(act_ids.cpu().numpy(), ids)
+    z = oracle_mod.logits(h, W_bits[ids])
+    check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, ids, k, name)
