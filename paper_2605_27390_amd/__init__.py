@@ -22,3 +22,4 @@ from .binding import (  # noqa: F401
     active_lmhead_topk_segmented,
     validate_ids,
 )
+from .arc import ArcManager  # noqa: F401,E402

@@ -9,8 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libevospec.so")
-SOURCES = ["kernels.hip", "gemm.hip", "api.cpp"]
-HEADERS = ["plan.hpp", "launch.hpp", "common.hpp", os.path.join(ROOT, "include", "evospec.h")]
+SOURCES = ["kernels.hip", "gemm.hip", "api.cpp", "arc.cpp"]
+HEADERS = ["plan.hpp", "launch.hpp", "common.hpp", os.path.join(ROOT, "include", "evospec.h"),
+           os.path.join(ROOT, "include", "evospec_arc.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

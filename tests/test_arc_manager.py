@@ -1,0 +1,76 @@
+"""The C++ dynamic-buffer manager (through its C ABI) against the plain oracle: the same
+hand-worked trace, and identical writes and state, event by event, on random request streams
+with the paper's parameters.  Host only: no GPU needed."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import evospec_inputs as gi
+from oracle import ArcOracle
+from test_arc_oracle import run_trace
+
+
+@pytest.fixture(scope="module")
+def ArcManager():
+    import paper_2605_27390_amd as ev
+    return ev.ArcManager
+
+
+def test_hand_worked_trace(ArcManager):
+    run_trace(ArcManager)
+
+
+def same_state(a, b):
+    sa, sb = a.state(), b.state()
+    for key in ("p", "T1", "T2", "B1", "B2", "slots", "step", "events"):
+        assert sa[key] == sb[key], key
+    assert a.resident() == b.resident()
+
+
+@pytest.mark.parametrize("params", [
+    dict(),                                                      # the paper's setting
+    dict(capacity=16, p0=3, ghost_cap=5, max_insert=4, min_residency=2, warmup_events=0, slot_base=7),
+    dict(capacity=8, p0=8, ghost_cap=0, max_insert=8, min_residency=0, warmup_events=3),
+    dict(capacity=32, p0=0, ghost_cap=64, max_insert=1, min_residency=5, warmup_events=10),
+])
+def test_matches_the_oracle_event_by_event(ArcManager, params):
+    rng = np.random.default_rng(11)
+    V = 4000
+    core = gi.zipf_ranking(V, 5)[:300]
+    a, b = ArcManager(core=core, **params), ArcOracle(core=core, **params)
+    weights = gi.zipf_weights(V)
+    weights = weights / weights.sum()
+    perm = gi.zipf_ranking(V, 5)
+    for ev in range(1500):
+        n = int(rng.integers(0, 90))
+        cands = perm[rng.choice(V, size=n, p=weights)]           # Zipf-distributed token ids, repeats included
+        if ev % 97 == 0:
+            cands = np.concatenate([cands, [-1, -7]]).astype(np.int32)
+        assert a.event(cands) == b.event(cands), ev
+        if ev % 10 == 0:
+            same_state(a, b)
+        steps = int(rng.integers(0, 4))
+        a.advance(steps); b.advance(steps)
+        if rng.random() < 0.3:
+            t = perm[rng.choice(V, size=6, p=weights)]
+            a.touch(t); b.touch(t)
+    same_state(a, b)
+    assert len(a.resident()) == params.get("capacity", 256)
+
+
+def test_argument_errors(ArcManager):
+    import paper_2605_27390_amd as ev
+    L = ev.lib
+    with pytest.raises(ev.EvospecError):
+        ArcManager(capacity=0)
+    with pytest.raises(ev.EvospecError):
+        ArcManager(capacity=4, p0=5)
+    m = ArcManager(capacity=4, p0=2, max_insert=2)
+    n = ctypes.c_int(0)
+    assert L.evospec_arc_event(None, None, 0, None, None, ctypes.byref(n)) == 1
+    assert L.evospec_arc_event(m._h, None, 3, None, None, ctypes.byref(n)) == 1
+    assert L.evospec_arc_event(m._h, None, -1, None, None, ctypes.byref(n)) == 2
+    assert L.evospec_arc_advance(m._h, -1) == 2
+    assert L.evospec_arc_list(m._h, 4, None, 0, ctypes.byref(n)) == 2
+    assert m.event([]) == [] and m.state()["events"] == 1

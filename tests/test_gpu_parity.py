@@ -252,3 +252,41 @@ def test_segmented_small(ev, oracle_mod):
         check_head(v[r0:r1], i[r0:r1], l[r0:r1], z, union, k, f"seq {s}")
     ov, oi, ol = oracle_mod.active_lmhead_topk_segmented(h, W[core], core, W_arc, arcs, row_off, k)
     np.testing.assert_allclose(l, ol, rtol=1e-3)
+
+
+# ------------------------------------------------------------------ dynamic buffer -> gather -> head
+def test_arc_manager_drives_the_gather(ev, oracle_mod):
+    """Failure events go through the C++ buffer manager, its (slot, id) writes through
+    `active_gather`; the compact matrix must stay W_lm[ids] on every used slot and the head over
+    core + buffer must match the oracle on that active set."""
+    import torch
+    V, d, n_core, cap, k = 3000, 64, 500, 64, 10
+    W = gi.gen_W_lm(V, d)
+    core = gi.zipf_ranking(V, 21)[:n_core].astype(np.int32)
+    arc = ev.ArcManager(capacity=cap, p0=cap // 2, ghost_cap=cap, max_insert=32, min_residency=2, warmup_events=5,
+                        slot_base=n_core, core=core)
+    Wd = to_dev_bf16(W)
+    W_act = torch.zeros((n_core + cap, d), dtype=torch.bfloat16, device="cuda")
+    act_ids = torch.full((n_core + cap,), -1, dtype=torch.int32, device="cuda")
+    ev.active_gather(Wd, to_dev_i32(core), None, W_act, act_ids)
+    rng = np.random.default_rng(4)
+    h = gi.gen_h(20, d, 77)
+    for e in range(60):
+        slots, ids = arc.event_arrays(rng.integers(0, V, size=int(rng.integers(1, 50))))
+        if slots.size:
+            ev.active_gather(Wd, to_dev_i32(ids.copy()), to_dev_i32(slots.copy()), W_act, act_ids)
+        arc.advance(1)
+        if e in (3, 30, 59):
+            res = arc.resident()
+            n_act = n_core + len(res)
+            assert [s for s, _ in res] == list(range(n_core, n_act))
+            active = np.concatenate([core, np.array([t for _, t in res], dtype=np.int32)])
+            torch.cuda.synchronize()
+            assert np.array_equal(act_ids.cpu().numpy()[:n_act], active)
+            assert np.array_equal(bf16_dev_to_bits(W_act)[:n_act], W[active])
+            assert ev.validate_ids(act_ids[:n_act], V)
+            v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act[:n_act], act_ids[:n_act], k)
+            torch.cuda.synchronize()
+            check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), oracle_mod.logits(h, W[active]), active, k,
+                       f"event {e}")
+    assert len(arc.resident()) == cap
