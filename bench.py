@@ -230,6 +230,48 @@ def main() -> int:
                                  "rows_per_s": round(Mb / (seg_us * 1e-6), 1)}
         del W_core, W_arc, ws_b
 
+    if not args.no_extras and args.config == "draft60":
+        # the step before the path: the C++ dynamic-buffer manager (paper defaults) on a stream of
+        # failure events with Zipf-distributed candidates (20 seeds + up to 8 successors each, as
+        # the appendix forms them), and the gather it drives with its own update sizes
+        core_ids = ids0[:n_core]
+        arc = ev.ArcManager(slot_base=n_core, core=core_ids)
+        rng = np.random.default_rng(99)
+        wz = gi.zipf_weights(V)
+        wz = wz / wz.sum()
+        perm = gi.zipf_ranking(V, gi.SEED_IDS + c["cfg"])
+        n_events = 2000
+        cand_lists = [perm[rng.choice(V, size=int(rng.integers(20, 181)), p=wz)].astype(np.int32) for _ in range(n_events)]
+        sizes = []
+        t0 = time.perf_counter()
+        for cl in cand_lists:
+            s_, i_ = arc.event_arrays(cl)
+            sizes.append(int(s_.size))
+            arc.advance(3)
+        arc_s = time.perf_counter() - t0
+        W_tmp = torch.empty((n_core + 256, d), dtype=torch.bfloat16, device=dev)
+        I_tmp = torch.empty((n_core + 256,), dtype=torch.int32, device=dev)
+        arc2 = ev.ArcManager(slot_base=n_core, core=core_ids)
+        ups = []
+        for cl in cand_lists[:200]:
+            s_, i_ = arc2.event_arrays(cl)
+            arc2.advance(3)
+            if s_.size:
+                ups.append((torch.from_numpy(s_.copy()).to(dev), torch.from_numpy(i_.copy()).to(dev)))
+        g_us = timed(lambda i: ev.active_gather(W_lm, ups[i % len(ups)][1], ups[i % len(ups)][0], W_tmp, I_tmp), len(ups), warm=5)
+        extra["arc_manager"] = {"events_per_s": round(n_events / arc_s, 1), "us_per_event": round(arc_s / n_events * 1e6, 2),
+                                "mean_insertions_per_event": round(float(np.mean(sizes)), 2),
+                                "max_insertions_per_event": int(max(sizes)), "gather_us_per_event": round(g_us, 2)}
+        if not args.no_cpu_baseline:
+            import oracle
+            ref = oracle.ArcOracle(slot_base=n_core, core=core_ids)
+            t0 = time.perf_counter()
+            for cl in cand_lists[:300]:
+                ref.event(cl)
+                ref.advance(3)
+            extra["arc_manager"]["oracle_us_per_event"] = round((time.perf_counter() - t0) / 300 * 1e6, 2)
+        del W_tmp, I_tmp
+
     if args.sweep and args.config == "draft60":
         # the paper's own active-set sizes (Table 1 and the default setting), same rotation rule:
         # enough copies of W_act that the weights come from HBM

@@ -155,6 +155,35 @@ def arc_update(V: int, act_ids: np.ndarray, n_core: int, n_new: int, seed: int):
     return slots, new_ids
 
 
+def bigram_graph(V: int, seed: int, max_degree: int = 64, mean_degree: float = 12.0):
+    """A synthetic stand-in for the token co-occurrence graph (appendix, "Token co-occurrence
+    graph": bigram successors, at most 64 per source token, kept by decreasing weight) in CSR
+    form: (row_ptr int64 [V+1], col_idx int32).  Out-degrees are geometric, capped; successors are
+    drawn Zipf-weighted without repetition; their stored order stands for decreasing weight."""
+    rng = _rng(seed, 7)
+    deg = np.minimum(rng.geometric(1.0 / mean_degree, size=V) - 1, max_degree).astype(np.int64)
+    row_ptr = np.zeros(V + 1, dtype=np.int64)
+    np.cumsum(deg, out=row_ptr[1:])
+    w = zipf_weights(V)
+    cdf = np.cumsum(w / w.sum())
+    rank = zipf_ranking(V, seed)
+    draws = rank[np.minimum(np.searchsorted(cdf, rng.random(int(row_ptr[-1]) * 2)), V - 1)].astype(np.int32)
+    col = np.empty(int(row_ptr[-1]), dtype=np.int32)
+    pos = 0
+    for u in range(V):                                            # distinct successors per source
+        need, got, seen = int(deg[u]), 0, set()
+        while got < need:
+            if pos >= draws.shape[0]:
+                draws = rank[np.minimum(np.searchsorted(cdf, rng.random(4096)), V - 1)].astype(np.int32)
+                pos = 0
+            y = int(draws[pos]); pos += 1
+            if y != u and y not in seen:
+                seen.add(y)
+                col[row_ptr[u] + got] = y
+                got += 1
+    return row_ptr, col
+
+
 def checksum(a: np.ndarray) -> int:
     """64-bit FNV-style fold of the raw bytes (to show two runs consumed the same bits)."""
     b = np.ascontiguousarray(a).view(np.uint8).ravel()

@@ -18,3 +18,4 @@ from .oracle import (  # noqa: F401
     set_num_threads,
 )
 from .arc_oracle import ArcOracle  # noqa: F401,E402
+from .candidates_oracle import exact_mips, form_candidates  # noqa: F401,E402
