@@ -262,6 +262,26 @@ def main() -> int:
         extra["arc_manager"] = {"events_per_s": round(n_events / arc_s, 1), "us_per_event": round(arc_s / n_events * 1e6, 2),
                                 "mean_insertions_per_event": round(float(np.mean(sizes)), 2),
                                 "max_insertions_per_event": int(max(sizes)), "gather_us_per_event": round(g_us, 2)}
+        # a whole failure event of Path A: exact inner-product search over the full vocabulary
+        # (M = 1, top 10), candidates from a synthetic co-occurrence graph, admission, gather
+        row_ptr, col_idx = gi.bigram_graph(V, gi.SEED_IDS + 9)
+        arc3 = ev.ArcManager(slot_base=n_core, core=core_ids)
+        W_pa = torch.empty((n_core + 256, d), dtype=torch.bfloat16, device=dev)
+        I_pa = torch.empty((n_core + 256,), dtype=torch.int32, device=dev)
+        ws_pa = torch.empty(ev.path_a_workspace_bytes(V, d, 10, 32), dtype=torch.uint8, device=dev)
+        h_t = [dev_bf16(gi.gen_h(1, d, gi.SEED_H + 100 + j)) for j in range(8)]
+        tt = [rng.integers(0, V, 10).astype(np.int32) for _ in range(8)]
+        n_pa = 60
+        for j in range(5):
+            ev.path_a_event(arc3, h_t[j % 8], W_lm, tt[j % 8], 10, row_ptr, col_idx, 8, W_pa, I_pa, ws_pa)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for j in range(n_pa):
+            ev.path_a_event(arc3, h_t[j % 8], W_lm, tt[j % 8], 10, row_ptr, col_idx, 8, W_pa, I_pa, ws_pa)
+            arc3.advance(3)
+        torch.cuda.synchronize()
+        extra["path_a_event_us"] = round((time.perf_counter() - t0) / n_pa * 1e6, 1)
+        del W_pa, I_pa, ws_pa
         if not args.no_cpu_baseline:
             import oracle
             ref = oracle.ArcOracle(slot_base=n_core, core=core_ids)

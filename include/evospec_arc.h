@@ -75,6 +75,42 @@ int evospec_arc_list(const evospec_arc *arc, int which, int32_t *out, int cap, i
 /* Resident tokens ordered by slot: out_slots[i], out_ids[i], i < *n_out <= capacity. */
 int evospec_arc_resident(const evospec_arc *arc, int32_t *out_slots, int32_t *out_ids, int *n_out);
 
+/*
+ * Candidate formation of a failure event (Sec. "Semantic approximation", "Statistical
+ * expansion"; appendix "Runtime candidate formation"): seeds = target-side top candidates, then
+ * the retrieved nearest neighbours; every seed contributes its first `max_successors` (paper: 8)
+ * outgoing neighbours of the co-occurrence graph, given in CSR form (row_ptr[V + 1], col_idx; a
+ * row lists successors by decreasing weight); duplicates keep their first place.  Order: seeds,
+ * then successors seed by seed.  out[out_cap] receives at most out_cap ids, *n_out their number.
+ * Seeds outside [0, V) are dropped.  Host pointers only.
+ */
+int evospec_form_candidates(const int32_t *target_top, int n_target, const int32_t *mips_top, int n_mips,
+                            const int64_t *row_ptr, const int32_t *col_idx, int V, int max_successors,
+                            int32_t *out, int out_cap, int *n_out);
+
+/*
+ * One whole failure event of Path A (Algorithm 1, "Path A: Vocabulary Expansion") on the GPU
+ * and the host, for callers that run it on a side stream:
+ *   1. exact maximum-inner-product search: the n_mips (<= EVOSPEC_K_MAX) rows of W_lm with the
+ *      largest inner product with the target hidden state h_target (the fused head kernel at
+ *      M = 1 over the full vocabulary; the paper approximates this search with an HNSW index);
+ *   2. candidate formation (above) with the host arrays target_top / row_ptr / col_idx;
+ *   3. admission by the buffer manager `arc`;
+ *   4. evospec_active_gather of the admitted (slot, id) pairs into W_act / act_ids.
+ * h_target (bf16 [d]), W_lm (bf16 [V, d]), W_act, act_ids, workspace are device pointers, 16-byte
+ * aligned; everything else is host memory.  The call WAITS for step 1 on `stream` (it needs the
+ * ids on the host) and returns after the gather has been enqueued.  out_slots / out_ids (host,
+ * max_insert entries each, may be NULL) receive the admitted pairs, *n_out their number.
+ * workspace_bytes must be at least evospec_path_a_workspace_bytes(V, d, n_mips, max_insert).
+ */
+int evospec_path_a_workspace_bytes(int V, int d, int n_mips, int max_insert, size_t *out_bytes);
+int evospec_path_a_event(evospec_arc *arc, const void *h_target, int d, const void *W_lm, int V,
+                         const int32_t *target_top, int n_target, int n_mips,
+                         const int64_t *row_ptr, const int32_t *col_idx, int max_successors,
+                         void *W_act, int32_t *act_ids, int V_act,
+                         void *workspace, size_t workspace_bytes, void *stream,
+                         int32_t *out_slots, int32_t *out_ids, int *n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,4 +22,4 @@ from .binding import (  # noqa: F401
     active_lmhead_topk_segmented,
     validate_ids,
 )
-from .arc import ArcManager  # noqa: F401,E402
+from .arc import ArcManager, form_candidates, path_a_event, path_a_workspace_bytes  # noqa: F401,E402

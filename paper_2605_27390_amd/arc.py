@@ -35,6 +35,20 @@ lib.evospec_arc_resident.restype = ctypes.c_int
 lib.evospec_arc_resident.argtypes = [ctypes.c_void_p, _i32p, _i32p, ctypes.POINTER(ctypes.c_int)]
 
 
+_i64p = ctypes.POINTER(ctypes.c_int64)
+lib.evospec_form_candidates.restype = ctypes.c_int
+lib.evospec_form_candidates.argtypes = [_i32p, ctypes.c_int, _i32p, ctypes.c_int, _i64p, _i32p, ctypes.c_int,
+                                        ctypes.c_int, _i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+lib.evospec_path_a_workspace_bytes.restype = ctypes.c_int
+lib.evospec_path_a_workspace_bytes.argtypes = [ctypes.c_int] * 4 + [ctypes.POINTER(ctypes.c_size_t)]
+lib.evospec_path_a_event.restype = ctypes.c_int
+lib.evospec_path_a_event.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                                     _i32p, ctypes.c_int, ctypes.c_int, _i64p, _i32p, ctypes.c_int,
+                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                     ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                     _i32p, _i32p, ctypes.POINTER(ctypes.c_int)]
+
+
 def _ptr(a: np.ndarray):
     return a.ctypes.data_as(_i32p)
 
@@ -103,3 +117,45 @@ class ArcManager:
         return {"p": int(z[0]), "T1": self._list(0, self.capacity), "T2": self._list(1, self.capacity),
                 "B1": self._list(2, self.ghost_cap), "B2": self._list(3, self.ghost_cap),
                 "slots": {t: s for s, t in self.resident()}, "step": int(z[5]), "events": int(z[6])}
+
+
+def form_candidates(target_top, mips_top, row_ptr, col_idx, V, max_successors=8, cap=4096):
+    """Ordered, de-duplicated candidate ids of one failure event (host arrays in, list out)."""
+    t = np.ascontiguousarray(np.asarray(target_top, dtype=np.int32))
+    m = np.ascontiguousarray(np.asarray(mips_top, dtype=np.int32))
+    rp = np.ascontiguousarray(np.asarray(row_ptr, dtype=np.int64))
+    ci = np.ascontiguousarray(np.asarray(col_idx, dtype=np.int32))
+    out = np.empty(max(1, cap), dtype=np.int32)
+    n = ctypes.c_int(0)
+    _check(lib.evospec_form_candidates(_ptr(t) if t.size else None, int(t.size), _ptr(m) if m.size else None, int(m.size),
+                                       rp.ctypes.data_as(_i64p), _ptr(ci) if ci.size else None, int(V), int(max_successors),
+                                       _ptr(out), int(cap), ctypes.byref(n)), "evospec_form_candidates")
+    return out[:n.value].tolist()
+
+
+def path_a_workspace_bytes(V, d, n_mips, max_insert):
+    out = ctypes.c_size_t(0)
+    _check(lib.evospec_path_a_workspace_bytes(int(V), int(d), int(n_mips), int(max_insert), ctypes.byref(out)),
+           "evospec_path_a_workspace_bytes")
+    return int(out.value)
+
+
+def path_a_event(arc, h_target, W_lm, target_top, n_mips, row_ptr, col_idx, max_successors, W_act, act_ids, workspace):
+    """One failure event (search, candidates, admission, gather) on torch's current stream; returns
+    the admitted (slot, id) pairs.  Tensors are CUDA tensors; row_ptr / col_idx / target_top host arrays."""
+    import torch
+    t = np.ascontiguousarray(np.asarray(target_top, dtype=np.int32))
+    rp = np.ascontiguousarray(np.asarray(row_ptr, dtype=np.int64))
+    ci = np.ascontiguousarray(np.asarray(col_idx, dtype=np.int32))
+    V, d = W_lm.shape
+    cap = max(1, arc.max_insert)
+    slots, ids = np.empty(cap, dtype=np.int32), np.empty(cap, dtype=np.int32)
+    n = ctypes.c_int(0)
+    _check(lib.evospec_path_a_event(arc._h, h_target.data_ptr(), int(d), W_lm.data_ptr(), int(V),
+                                    _ptr(t) if t.size else None, int(t.size), int(n_mips),
+                                    rp.ctypes.data_as(_i64p), _ptr(ci) if ci.size else None, int(max_successors),
+                                    W_act.data_ptr(), act_ids.data_ptr(), int(W_act.shape[0]),
+                                    workspace.data_ptr(), int(workspace.numel()),
+                                    torch.cuda.current_stream().cuda_stream, _ptr(slots), _ptr(ids), ctypes.byref(n)),
+           "evospec_path_a_event")
+    return list(zip(slots[:n.value].tolist(), ids[:n.value].tolist()))

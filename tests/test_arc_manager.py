@@ -74,3 +74,23 @@ def test_argument_errors(ArcManager):
     assert L.evospec_arc_advance(m._h, -1) == 2
     assert L.evospec_arc_list(m._h, 4, None, 0, ctypes.byref(n)) == 2
     assert m.event([]) == [] and m.state()["events"] == 1
+
+
+def test_candidate_formation_matches_the_oracle():
+    import paper_2605_27390_amd as ev
+    from oracle import form_candidates
+    V = 6000
+    row_ptr, col = gi.bigram_graph(V, 8)
+    rng = np.random.default_rng(2)
+    for trial in range(200):
+        t = rng.integers(0, V, int(rng.integers(0, 12)))
+        m = rng.integers(0, V, int(rng.integers(0, 12)))
+        ms = int(rng.integers(0, 10))
+        cap = int(rng.choice([4096, 5, 25, 0]))
+        assert ev.form_candidates(t, m, row_ptr, col, V, ms, cap) == form_candidates(t, m, row_ptr, col, ms, cap), trial
+    # the hand-worked case of the oracle's pins
+    rp = np.array([0, 3, 3, 7, 8, 8, 8, 8, 8, 8, 8], dtype=np.int64)
+    ci = np.array([5, 6, 7, 6, 0, 9, 8, 1], dtype=np.int32)
+    assert ev.form_candidates([2, 0], [0, 3], rp, ci, 10, 2) == [2, 0, 3, 6, 5, 1]
+    # seeds outside the vocabulary are dropped
+    assert ev.form_candidates([2, 10, -1], [3], rp, ci, 10, 0) == [2, 3]

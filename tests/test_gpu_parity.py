@@ -290,3 +290,48 @@ def test_arc_manager_drives_the_gather(ev, oracle_mod):
             check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), oracle_mod.logits(h, W[active]), active, k,
                        f"event {e}")
     assert len(arc.resident()) == cap
+
+
+def test_path_a_event_end_to_end(ev, oracle_mod):
+    """A failure event through the native entry point (exact inner-product search on the GPU,
+    candidate formation, admission, gather) against the same steps done by the oracles."""
+    import torch
+    from oracle import ArcOracle, exact_mips, form_candidates
+    V, d, n_core, cap = 5000, 128, 800, 64
+    W = gi.gen_W_lm(V, d)
+    core = gi.zipf_ranking(V, 31)[:n_core].astype(np.int32)
+    row_ptr, col = gi.bigram_graph(V, 12)
+    params = dict(capacity=cap, p0=cap // 2, ghost_cap=cap, max_insert=32, min_residency=1, warmup_events=2,
+                  slot_base=n_core, core=core)
+    arc, ref = ev.ArcManager(**params), ArcOracle(**params)
+    Wd = to_dev_bf16(W)
+    W_act = torch.zeros((n_core + cap, d), dtype=torch.bfloat16, device="cuda")
+    act_ids = torch.full((n_core + cap,), -1, dtype=torch.int32, device="cuda")
+    ev.active_gather(Wd, to_dev_i32(core), None, W_act, act_ids)
+    ws = torch.empty(ev.path_a_workspace_bytes(V, d, 10, 32), dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(8)
+    for e in range(12):
+        h = gi.gen_h(1, d, 500 + e)
+        target_top = rng.integers(0, V, 10).astype(np.int32)
+        hd = to_dev_bf16(h)
+        # the search alone, checked against the exact fp64 search (near-ties at the cut exempt)
+        v, i, l = ev.active_lmhead_topk(hd, Wd, None, 10)
+        torch.cuda.synchronize()
+        z = oracle_mod.logits(h, W)
+        check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, np.arange(V, dtype=np.int32), 10, f"search {e}")
+        exact = exact_mips(h, W, 11)
+        gap = abs(z[0, exact[9]] - z[0, exact[10]]) / max(abs(z[0, exact[9]]), abs(z[0, exact[10]]))
+        if gap > 1e-3:
+            assert set(i[0].cpu().numpy().tolist()) == set(exact[:10].tolist())
+        # the event: its writes are what the oracles derive from the GPU's own neighbours
+        got = ev.path_a_event(arc, hd, Wd, target_top, 10, row_ptr, col, 8, W_act, act_ids, ws)
+        want = ref.event(form_candidates(target_top, i[0].cpu().numpy(), row_ptr, col, 8))
+        assert got == want, e
+        arc.advance(1); ref.advance(1)
+    torch.cuda.synchronize()
+    res = ref.resident()
+    n_act = n_core + len(res)
+    active = np.concatenate([core, np.array([t for _, t in res], dtype=np.int32)])
+    assert np.array_equal(act_ids.cpu().numpy()[:n_act], active)
+    assert np.array_equal(bf16_dev_to_bits(W_act)[:n_act], W[active])
+    assert len(res) == cap
