@@ -180,7 +180,7 @@ int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, c
         const GemmPlan gp = make_gemm_plan(M, V_act, k);
         hipError_t e = launch_gemm_partials(h, M, d, W_act, ids, V_act, k, ws + gp.keys_off, ws + gp.stats_off, st);
         if (e != hipSuccess) return hip_fail(e);
-        MergeSet a{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len};
+        MergeSet a{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len, true};
         MergeSet none{};
         e = launch_merge(a, none, k, out_vals, out_ids, out_logz, 0, M, st);
         return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
@@ -239,7 +239,7 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
         hipError_t e = launch_gemm_partials(h, M, d, W_core, ids_core, V_core, k, ws + gp.keys_off,
                                             ws + gp.stats_off, st);
         if (e != hipSuccess) return hip_fail(e);
-        core = MergeSet{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len};
+        core = MergeSet{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len, true};
     } else if (V_core > 0) {
         const Plan pc = make_plan(kMTile, V_core, k, num_cu);
         for (int m0 = 0, pss = 0; m0 < M; m0 += kMTile, ++pss) {

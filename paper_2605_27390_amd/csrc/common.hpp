@@ -33,13 +33,15 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// One set of per-slab partial results as the merge kernel reads it.
+// One set of per-slab partial results as the merge kernel reads it: the list of (slab L, row
+// slot r) starts at keys + L * key_slab + r * key_row, its statistics are stats[L * stat_slab + r * stat_row].
 struct PartialSet {
-    const u64* keys;        // [n_slabs][row_stride][list_len]
-    const float2* stats;    // [n_slabs][row_stride]
+    const u64* keys;
+    const float2* stats;
     int n_slabs;
     int row_base;           // slot of this launch's block 0 inside the set's row dimension
-    int row_stride;         // draft-row slots per slab in the layout
+    size_t key_slab, key_row;       // strides in u64
+    size_t stat_slab, stat_row;     // strides in float2
     int list_len;           // key slots per list (>= k); empty slots hold 0
     int sorted;             // lists hold keys, descending (slot 0 is the maximum); else (logit, id)
                             // pairs in any order, all ones = empty

@@ -227,6 +227,7 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
     const int nvalid = min(kGemmSlab, V_act - vrow0);
     if (nvalid <= 0) return;                                       // quadrant wholly past the active set
     const int slab = tile_v * (kGemmTile / kGemmSlab) + wv;
+    const int n_slabs = (V_act + kGemmSlab - 1) / kGemmSlab;    // lists are laid out [draft row][slab][slot]
     unsigned char* my = smem + (size_t)w * kGEpiBytes;
     // common path: [8][16][16] staged lists of all blocks, then one spare slot per lane;
     // rare path (afterwards, same bytes): [16][128] full lists of one block, then [64][32] parked logits
@@ -370,7 +371,7 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
     const int mrow0 = m0 + wm * 128 + n16;                         // draft row of block 0
 #pragma unroll
     for (int mb = 0; mb < 8; ++mb)
-        if (g == 0 && mrow0 + 16 * mb < M) part_stats[(size_t)slab * M + mrow0 + 16 * mb] = make_float2(vm[mb], se[mb]);
+        if (g == 0 && mrow0 + 16 * mb < M) part_stats[(size_t)(mrow0 + 16 * mb) * n_slabs + slab] = make_float2(vm[mb], se[mb]);
 
     // survivors per lane (<= 32), four blocks to a register; from the 4 lanes of a row: the offset
     // of this lane's survivors in the row's list and the list length L (<= 128), still packed
@@ -438,7 +439,7 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
             const int m = m0 + wm * 128 + 16 * mb + r16;
             const u32x4 q = *reinterpret_cast<const u32x4*>(my + (it * 64 + lane) * 16);
             if (((fast >> mb) & 1u) && m < M)
-                *reinterpret_cast<u32x4*>(part_keys + ((size_t)slab * M + m) * kGFastLen + 2 * (lane & 7)) = q;
+                *reinterpret_cast<u32x4*>(part_keys + ((size_t)m * n_slabs + slab) * kGFastLen + 2 * (lane & 7)) = q;
         }
     }
 #undef EVOSPEC_MB
@@ -473,7 +474,7 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
             if ((mk >> i) & 1u) mine[pos++] = make_key(zbuf[i], Ids[(i >> 2) * 16 + 4 * g + (i & 3)]);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        u64* dst = part_keys + ((size_t)slab * M + (m_ok ? m : 0)) * list_len;
+        u64* dst = part_keys + ((size_t)(m_ok ? m : 0) * n_slabs + slab) * list_len;
         for (int e = g; e < L; e += 4) {
             const u64 key = mine[e];
             int rank = 0;

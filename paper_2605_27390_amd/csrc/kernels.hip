@@ -428,15 +428,18 @@ __device__ __forceinline__ u64 wave_bcast(u64 x, int src_lane /*uniform*/) {
 
 __global__ void __launch_bounds__(kMergeThreads)
 lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_keys, size_t a_pass_stats,
-                    size_t b_chunk_keys, size_t b_chunk_stats, int k,
+                    size_t b_chunk_keys, size_t b_chunk_stats, int k, int pend_cap,
                     float* __restrict__ out_vals, int32_t* __restrict__ out_ids,
                     float* __restrict__ out_logz) {
     constexpr int NT = kMergeThreads;
     constexpr int NWV = NT / 64;
     __shared__ u64 run[2][kKMax];                    // running k best, descending
     __shared__ u64 cand[(NWV + 1) * kKMax];          // per-wave best heads, then the running list
-    constexpr int kPendCap = kKMax * kKMax + kKMax;
-    __shared__ u64 pend[kPendCap];                   // entries that reach the bound
+    // entries that reach the bound: at most k lists of max_len entries, plus the running k
+    // (dynamic LDS, sized by the launcher, so that small k leaves room for many workgroups per CU)
+    extern __shared__ __align__(16) unsigned char merge_smem[];
+    u64* pend = reinterpret_cast<u64*>(merge_smem);
+    const int kPendCap = pend_cap;
     __shared__ const u64* qual[kKMax];             // lists whose head reaches the bound
     __shared__ int qual_len[kKMax];
     __shared__ u64 tau_s;
@@ -456,8 +459,8 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
     const int total = A.n_slabs + B.n_slabs;
 
     auto list_of = [&](int L) -> const u64* {
-        return L < A.n_slabs ? A.keys + ((size_t)L * A.row_stride + slotA) * A.list_len
-                             : B.keys + ((size_t)(L - A.n_slabs) * B.row_stride + slotB) * B.list_len;
+        return L < A.n_slabs ? A.keys + (size_t)L * A.key_slab + (size_t)slotA * A.key_row
+                             : B.keys + (size_t)(L - A.n_slabs) * B.key_slab + (size_t)slotB * B.key_row;
     };
     auto len_of = [&](int L) { return L < A.n_slabs ? A.list_len : B.list_len; };
     auto sorted_of = [&](int L) { return (L < A.n_slabs ? A.sorted : B.sorted) != 0; };
@@ -468,11 +471,16 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
         if (sorted_of(L)) return p[0];
         u64 hd = 0;
         const int n = len_of(L);
-        for (int j = 0; j < n; j += 2) {
-            const u32x4 q = *(gvec_ptr)(p + j);
-            const u64 k0 = pair_key(q[1], q[0]), k1 = pair_key(q[3], q[2]);
-            hd = k0 > hd ? k0 : hd;
-            hd = k1 > hd ? k1 : hd;
+        for (int j0 = 0; j0 < n; j0 += 16) {            // 8 loads in flight (list lengths are 16, 32 or 64)
+            u32x4 q[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) q[u] = *(gvec_ptr)(p + j0 + 2 * u);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const u64 k0 = pair_key(q[u][1], q[u][0]), k1 = pair_key(q[u][3], q[u][2]);
+                hd = k0 > hd ? k0 : hd;
+                hd = k1 > hd ? k1 : hd;
+            }
         }
         return hd;
     };
@@ -483,8 +491,8 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
     // ---- log-normaliser: online (max, scaled sum) per thread, fixed-shape reduction
     float mx = -INFINITY, sm = 0.f;
     for (int t = tid; t < total; t += NT) {
-        const float2 st = t < A.n_slabs ? A.stats[(size_t)t * A.row_stride + slotA]
-                                        : B.stats[(size_t)(t - A.n_slabs) * B.row_stride + slotB];
+        const float2 st = t < A.n_slabs ? A.stats[(size_t)t * A.stat_slab + (size_t)slotA * A.stat_row]
+                                        : B.stats[(size_t)(t - A.n_slabs) * B.stat_slab + (size_t)slotB * B.stat_row];
         const float nm = fmaxf(mx, st.x);
         sm = (mx == -INFINITY ? 0.f : sm * __expf(mx - nm)) + st.y * __expf(st.x - nm);
         mx = nm;
@@ -648,15 +656,31 @@ hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const Merg
     int max_rows = 0;
     for (int i = 0; i < cb.n; ++i) max_rows = cb.rows[i] > max_rows ? cb.rows[i] : max_rows;
     if (max_rows == 0) return hipSuccess;
-    if ((a.list_len != 0 && (a.list_len < k || a.list_len > kKMax || (a.list_len & 1))) ||
-        (b.list_len != 0 && (b.list_len < k || b.list_len > kKMax || (b.list_len & 1))))
+    if ((a.list_len != 0 && (a.list_len < k || a.list_len > kKMax || (a.list_len & 15))) ||
+        (b.list_len != 0 && (b.list_len < k || b.list_len > kKMax || (b.list_len & 15))))
         return hipErrorInvalidValue;
-    PartialSet A{static_cast<const u64*>(a.keys), static_cast<const float2*>(a.stats), a.n_slabs, a.row_base, a.row_stride,
-                 a.list_len ? a.list_len : k, a.list_len == 0};
-    PartialSet B{static_cast<const u64*>(b.keys), static_cast<const float2*>(b.stats), b.n_slabs, b.row_base, b.row_stride,
-                 b.list_len ? b.list_len : k, b.list_len == 0};
-    hipLaunchKernelGGL(lmhead_merge_kernel, dim3(max_rows, cb.n), dim3(kMergeThreads), 0, stream, A, B, cb,
-                       a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k,
+    auto as_set = [&](const MergeSet& m) {
+        PartialSet p;
+        p.keys = static_cast<const u64*>(m.keys);
+        p.stats = static_cast<const float2*>(m.stats);
+        p.n_slabs = m.n_slabs;
+        p.row_base = m.row_base;
+        p.list_len = m.list_len ? m.list_len : k;
+        p.sorted = m.list_len == 0;
+        if (m.row_major) {          // [row][slab][slot]: one row's lists are contiguous
+            p.key_slab = (size_t)p.list_len; p.key_row = (size_t)m.n_slabs * p.list_len;
+            p.stat_slab = 1; p.stat_row = (size_t)m.n_slabs;
+        } else {                    // [slab][row][slot]
+            p.key_slab = (size_t)m.row_stride * p.list_len; p.key_row = (size_t)p.list_len;
+            p.stat_slab = (size_t)m.row_stride; p.stat_row = 1;
+        }
+        return p;
+    };
+    const PartialSet A = as_set(a), B = as_set(b);
+    const int max_len = A.list_len > B.list_len ? A.list_len : B.list_len;
+    const int pend_cap = k * max_len + k + 8;      // k qualifying lists in full, the running k (8-byte keys: < 34 KB)
+    hipLaunchKernelGGL(lmhead_merge_kernel, dim3(max_rows, cb.n), dim3(kMergeThreads), (size_t)pend_cap * 8, stream, A, B, cb,
+                       a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k, pend_cap,
                        out_vals, out_ids, out_logz);
     return hipGetLastError();
 }

@@ -13,10 +13,11 @@ struct MergeSet {
     const void* stats = nullptr;    // float2 [n_slabs][row_stride]
     int n_slabs = 0;
     int row_base = 0;               // slot of the launch's first row inside the set
-    int row_stride = 64;            // draft-row slots per slab in the layout
+    int row_stride = 64;            // draft-row slots per slab in the layout (slab-major sets)
     int list_len = 0;               // slots per list; 0 = k keys, descending.  Otherwise the slots hold
                                     // the slab's candidates as (logit bits << 32 | id) in any order,
                                     // all ones = empty
+    bool row_major = false;         // true: [row][slab][slot] (large-M path), row_stride unused
 };
 
 // Where the chunks of a batched launch find their operands and leave their partials: chunk i reads
@@ -39,8 +40,8 @@ hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const Merg
 hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
                            const int32_t* ids, int V_act, int k, void* keys, void* stats,
                            hipStream_t stream);
-// Large-M path: partials of all M draft rows, keys u64 [ceil(V_act/128)][M][gemm_list_len(k)] in any
-// order, stats float2 [..][M].
+// Large-M path: partials of all M draft rows, row-major: keys u64 [M][ceil(V_act/128)][gemm_list_len(k)]
+// in any order, stats float2 [M][ceil(V_act/128)].
 hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, const int32_t* ids, int V_act,
                                 int k, void* keys, void* stats, hipStream_t stream);
 hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
