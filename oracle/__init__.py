@@ -19,3 +19,4 @@ from .oracle import (  # noqa: F401
 )
 from .arc_oracle import ArcOracle  # noqa: F401,E402
 from .candidates_oracle import exact_mips, form_candidates  # noqa: F401,E402
+from .kl_gate_oracle import kl_gate  # noqa: F401,E402
