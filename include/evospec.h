@@ -133,6 +133,23 @@ int evospec_active_lmhead_topk_segmented(const void *h, int M, int d,
         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Retained-support KL gate of Path B (Sec. "Online parameter update", Eq. 5 and the admission
+ * rule; Algorithm 1, Path B).  For each of E verification events: support = the ids of the K
+ * (paper: K_logit = 256; 1 <= K <= EVOSPEC_KL_K_MAX, K <= V) largest target logits, ties to the
+ * smaller id, by decreasing logit; z_q[i] = h_draft . W_lm[support[i]] (Eq. 1, bf16 in, fp32
+ * accumulate); p = Softmax(z_t / T), q = Softmax(z_q / T) on the support; out_kl[e] = D_KL(p || q).
+ * The caller compares out_kl with the gate (paper: 0.1).
+ *   z_target  dev fp32 [E, V]         h_draft  dev bf16 [E, d], 16-B aligned
+ *   W_lm      dev bf16 [V, d], 16-B aligned, d % 8 == 0, d <= 24,576
+ *   out_support dev int32 [E, K]; out_target_logits, out_draft_logits dev fp32 [E, K]; out_kl dev fp32 [E]
+ * T > 0.  No workspace, no synchronisation; E == 0 is a no-op.
+ */
+#define EVOSPEC_KL_K_MAX 256
+int evospec_kl_gate(const float *z_target, int E, int V, const void *h_draft, int d, const void *W_lm,
+                    int K, float T, int32_t *out_support, float *out_target_logits,
+                    float *out_draft_logits, float *out_kl, void *stream);
+
+/*
  * Debug aid: checks 0 <= ids[i] < V and that no id occurs twice (Eq. 3 is a set).
  * Launches one check kernel and waits for it (the only call that synchronises).
  * Returns EVOSPEC_OK or EVOSPEC_INVALID_IDS.  ids dev int32 [n].

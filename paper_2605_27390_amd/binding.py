@@ -56,6 +56,8 @@ def _load() -> ctypes.CDLL:
     L.evospec_active_lmhead_topk_segmented.argtypes = [vp, ci, ci, vp, vp, ci, vp, vp, ci,
                                                        ctypes.POINTER(ctypes.c_int32), ci, ci,
                                                        vp, vp, vp, vp, sz, vp]
+    L.evospec_kl_gate.restype = ci
+    L.evospec_kl_gate.argtypes = [vp, ci, ci, vp, ci, vp, ci, ctypes.c_float, vp, vp, vp, vp, vp]
     L.evospec_validate_ids.restype = ci
     L.evospec_validate_ids.argtypes = [vp, ci, ci, vp]
     return L
@@ -223,3 +225,22 @@ def validate_ids(ids, V: int) -> bool:
         return False
     _check(st, "evospec_validate_ids")
     return True
+
+
+def kl_gate(z_target, h_draft, W_lm, K=256, T=1.0, out_support=None, out_zt=None, out_zq=None, out_kl=None):
+    """Retained-support KL gate (Path B): returns (support int32 [E,K], target logits, draft logits
+    fp32 [E,K], kl fp32 [E]).  z_target fp32 [E,V], h_draft bf16 [E,d], W_lm bf16 [V,d], all on the GPU."""
+    import torch
+    E, V = z_target.shape
+    d = W_lm.shape[1]
+    dev = z_target.device
+    assert z_target.dtype == torch.float32 and z_target.is_contiguous() and h_draft.is_contiguous() and W_lm.is_contiguous()
+    if out_support is None:
+        out_support = torch.empty((E, K), dtype=torch.int32, device=dev)
+        out_zt = torch.empty((E, K), dtype=torch.float32, device=dev)
+        out_zq = torch.empty((E, K), dtype=torch.float32, device=dev)
+        out_kl = torch.empty((E,), dtype=torch.float32, device=dev)
+    _check(lib.evospec_kl_gate(z_target.data_ptr(), int(E), int(V), h_draft.data_ptr(), int(d), W_lm.data_ptr(),
+                               int(K), float(T), out_support.data_ptr(), out_zt.data_ptr(), out_zq.data_ptr(),
+                               out_kl.data_ptr(), torch.cuda.current_stream().cuda_stream), "evospec_kl_gate")
+    return out_support, out_zt, out_zq, out_kl
