@@ -282,6 +282,14 @@ def main() -> int:
         torch.cuda.synchronize()
         extra["path_a_event_us"] = round((time.perf_counter() - t0) / n_pa * 1e6, 1)
         del W_pa, I_pa, ws_pa
+        # Path B admission gate: 60 verification events, top-256 support over the full vocabulary
+        E_kl = 60
+        z_t = torch.randn((E_kl, V), dtype=torch.float32, device=dev) * 2.0
+        h_kl = dev_bf16(gi.gen_h(E_kl, d, gi.SEED_H + 70))
+        kl_out = ev.kl_gate(z_t, h_kl, W_lm, 256, 1.0)
+        kl_us = timed(lambda i: ev.kl_gate(z_t, h_kl, W_lm, 256, 1.0, *kl_out), 30, warm=3)
+        extra["kl_gate_60x256_us"] = round(kl_us, 1)
+        del z_t
         if not args.no_cpu_baseline:
             import oracle
             ref = oracle.ArcOracle(slot_base=n_core, core=core_ids)

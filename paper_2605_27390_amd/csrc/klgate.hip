@@ -5,9 +5,12 @@
 // when D_KL(p || q) exceeds the gate.
 //
 // One workgroup of 16 wavefronts per event, everything in one launch:
-//  1. exact selection of the K largest (logit, id) keys by radix select on the 64-bit sortable
-//     key (11 bits per pass, histogram in LDS; a pass is skipped as soon as the bin that holds the
-//     K-th key is taken whole), then a sweep that collects them and a rank-by-counting sort;
+//  1. exact selection of the K largest (logit, id) keys.  Common path, two sweeps: every thread
+//     takes the maximum of its share; the K-th largest of these 1024 maxima is a lower bound of the
+//     K-th largest key, so the keys that reach it (a few hundred) are collected and ranked by
+//     counting.  If more than 2048 reach it (masses of equal logits), radix select on the 64-bit
+//     key instead (11 bits per pass, histogram in LDS, a pass is skipped as soon as the bin that
+//     holds the K-th key is taken whole), then a collecting sweep and the same ranking;
 //  2. draft logits: one wavefront per support row, 16 bytes per lane and load, h in LDS;
 //  3. log-sum-exp of both logit vectors and the divergence, by one wavefront.
 // Latency bound: per event it reads the target logits a few times (they stay in L2) and K rows
@@ -26,6 +29,7 @@ constexpr int kKlWaves = kKlThreads / 64;
 constexpr int kKlMaxK = 256;
 constexpr int kKlBits = 11;
 constexpr int kKlBins = 1 << kKlBits;
+constexpr int kKlCand = 2048;                 // candidates the common path can rank
 
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
@@ -48,6 +52,9 @@ kl_gate_kernel(const float* __restrict__ z_target, int V, const uint16_t* __rest
     uint16_t* hs = reinterpret_cast<uint16_t*>(kl_smem);            // [d] draft hidden state
     __shared__ uint32_t hist[kKlBins];
     __shared__ u64 sel[kKlMaxK], sorted[kKlMaxK];
+    __shared__ u64 tmax[kKlThreads], cand[kKlCand];
+    __shared__ u64 tau0_s;
+    __shared__ int ncand;
     __shared__ float zq_s[kKlMaxK];
     __shared__ uint32_t lane_tot[64];
     __shared__ u64 prefix_s;
@@ -59,8 +66,43 @@ kl_gate_kernel(const float* __restrict__ z_target, int V, const uint16_t* __rest
 
     for (int i = tid; i < d / 8; i += kKlThreads)
         reinterpret_cast<u32x4*>(hs)[i] = *(gvec_ptr)(h_draft + (size_t)e * d + 8 * i);
-    if (tid == 0) { prefix_s = 0; need_s = K; nsel = 0; done_s = 0; }
+    if (tid == 0) { prefix_s = 0; need_s = K; nsel = 0; done_s = 0; ncand = 0; tau0_s = 0; }
+
+    // ---- 1a. common path: bound from the per-thread maxima
+    {
+        u64 mx = 0;
+        for (int i = tid; i < V; i += kKlThreads) {
+            const u64 key = make_key(z[i], i);
+            mx = key > mx ? key : mx;
+        }
+        tmax[tid] = mx;
+    }
     __syncthreads();
+    {
+        const u64 mine = tmax[tid];
+        int r = 0;
+        for (int j = 0; j < kKlThreads; ++j) r += tmax[j] > mine ? 1 : 0;
+        if (mine != 0 && r == K - 1) tau0_s = mine;              // keys are distinct: one thread at most
+    }
+    __syncthreads();
+    const u64 tau0 = tau0_s;                                     // 0: fewer than K threads saw a key
+    for (int i = tid; i < V; i += kKlThreads) {
+        const u64 key = make_key(z[i], i);
+        if (key >= tau0) {
+            const int p = atomicAdd(&ncand, 1);
+            if (p < kKlCand) cand[p] = key;
+        }
+    }
+    __syncthreads();
+    const int nc = ncand;
+    if (nc <= kKlCand) {
+        for (int t = tid; t < nc; t += kKlThreads) {
+            const u64 mine = cand[t];
+            int r = 0;
+            for (int j = 0; j < nc; ++j) r += cand[j] > mine ? 1 : 0;
+            if (r < K) sorted[r] = mine;
+        }
+    } else {
 
     // ---- 1. radix select: after a pass, prefix holds the top `done` bits of the K-th largest key
     // and need the number of keys still to take among those that share them
@@ -121,26 +163,43 @@ kl_gate_kernel(const float* __restrict__ z_target, int V, const uint16_t* __rest
         for (int j = 0; j < K; ++j) r += sel[j] > mine ? 1 : 0;
         sorted[r] = mine;
     }
+    }   // radix path
     __syncthreads();
 
-    // ---- 2. draft logits on the support: wavefront w takes rows w, w + 16, ...
-    for (int r = w; r < K; r += kKlWaves) {
-        const uint16_t* row = W_lm + (size_t)key_id(sorted[r]) * d;
-        float acc = 0.f;
+    // ---- 2. draft logits on the support: wavefront w takes rows w, w + 16, ..., four at a time so
+    // that their loads are in flight together
+    for (int r0 = w; r0 < K; r0 += 4 * kKlWaves) {
+        const uint16_t* row[4];
+        float acc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = r0 + u * kKlWaves;
+            row[u] = W_lm + (size_t)key_id(sorted[r < K ? r : r0]) * d;      // past the end: a valid row again
+            acc[u] = 0.f;
+        }
         for (int p0 = 0; p0 < d / 8; p0 += 64) {
-            const int p = p0 + lane;
-            if (p < d / 8) {
-                const u32x4 a = *(gvec_ptr)(row + 8 * p);
-                const u32x4 b = reinterpret_cast<const u32x4*>(hs)[p];
+            const int p = p0 + lane < d / 8 ? p0 + lane : d / 8 - 1;      // ragged end: clamp, then weigh by zero
+            const bool live = p0 + lane < d / 8;
+            u32x4 a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = *(gvec_ptr)(row[u] + 8 * p);
+            u32x4 b = reinterpret_cast<const u32x4*>(hs)[p];
+            if (!live) b = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    acc = fmaf(__uint_as_float(a[q] << 16), __uint_as_float(b[q] << 16), acc);
-                    acc = fmaf(__uint_as_float(a[q] & 0xffff0000u), __uint_as_float(b[q] & 0xffff0000u), acc);
+                    acc[u] = fmaf(__uint_as_float(a[u][q] << 16), __uint_as_float(b[q] << 16), acc[u]);
+                    acc[u] = fmaf(__uint_as_float(a[u][q] & 0xffff0000u), __uint_as_float(b[q] & 0xffff0000u), acc[u]);
                 }
             }
         }
-        acc = wave_sum(acc);
-        if (lane == 0) zq_s[r] = acc;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float t = wave_sum(acc[u]);
+            const int r = r0 + u * kKlWaves;
+            if (lane == 0 && r < K) zq_s[r] = t;
+        }
     }
     __syncthreads();
 
