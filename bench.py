@@ -2,9 +2,10 @@
 """Benchmark of the active-vocabulary LM head on one MI355X.
 
 A step is one pass of the whole hot path on one batch of synthetic input:
-  1. a dynamic-buffer update -- `evospec_active_gather` of 32 new rows into ARC slots of the
-     compact matrix (the paper caps insertions at 32 per failure event), then
-  2. `evospec_active_lmhead_topk`: restricted projection + log-normaliser + top-k + id remap.
+  1. the restricted head: projection + log-normaliser + top-k + id remap, and
+  2. a dynamic-buffer update -- 32 new rows into ARC slots of the compact matrix (the paper caps
+     insertions at 32 per failure event), applied behind the head and seen by the next step on that
+     matrix (`evospec_active_lmhead_topk_then_update`; the two separate calls are timed as an extra).
 All inputs are resident in HBM before the timed region.  Steps rotate over several copies of
 W_act so that every step streams its weights from HBM rather than from the memory-side cache.
 
@@ -106,10 +107,20 @@ def main() -> int:
     torch.cuda.synchronize()
 
     def step(i):
+        # the head on copy r as the previous update left it, and this step's update of the same
+        # copy applied behind it (seen by the copy's next step): two launches
         r = i % R
         if upd_slots:
             u = i // R
-            ev.active_gather(W_lm, upd_ids[u], upd_slots[u], W_acts[r], act_ids[r])
+            ev.active_lmhead_topk_then_update(h, W_acts[r], act_ids[r], k, W_lm, upd_ids[u], upd_slots[u],
+                                              out_v, out_i, out_l, ws)
+        else:
+            ev.active_lmhead_topk(h, W_acts[r], act_ids[r], k, out_v, out_i, out_l, ws)
+
+    def step_separate(i):
+        r = i % R
+        u = i // R
+        ev.active_gather(W_lm, upd_ids[u % len(upd_ids)], upd_slots[u % len(upd_ids)], W_acts[r], act_ids[r])
         ev.active_lmhead_topk(h, W_acts[r], act_ids[r], k, out_v, out_i, out_l, ws)
 
     # ---------------------------------------------------------------- timed region
@@ -177,6 +188,7 @@ def main() -> int:
         extra["head_us_cache_warm"] = round(timed(
             lambda i: ev.active_lmhead_topk(h, W_acts[0], act_ids[0], k, out_v, out_i, out_l, ws), n_ev), 2)
         if upd_slots:
+            extra["step_us_separate_calls"] = round(timed(step_separate, n_ev), 2)
             extra["gather32_us"] = round(timed(
                 lambda i: ev.active_gather(W_lm, upd_ids[0], upd_slots[0], W_acts[0], act_ids[0]), n_ev), 2)
         extra["gather_full_us"] = round(timed(

@@ -133,6 +133,21 @@ int evospec_active_lmhead_topk_segmented(const void *h, int M, int d,
         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The head (as evospec_active_lmhead_topk, on W_act / act_ids as they are), followed by a dynamic-
+ * buffer update of the same W_act / act_ids (as evospec_active_gather with these src_ids / slots / n),
+ * with one launch fewer: the update's rows are written by extra workgroups of the head's last launch,
+ * after everything that reads W_act has finished.  The result equals the two calls in that order.
+ * Meant for the decode loop: the ids a failure event admitted (App. "Additional safeguards": at most
+ * 32 per event) are applied behind the current draft step and seen by the next one (a late result
+ * "merges into a subsequent launch", App. "Retrieval latency and asynchronous execution").
+ */
+int evospec_active_lmhead_topk_then_update(const void *h, int M, int d, void *W_act, int32_t *act_ids,
+                                           int V_act, int k, float *out_vals, int32_t *out_ids, float *out_logz,
+                                           void *workspace, size_t workspace_bytes,
+                                           const void *W_lm, int V, const int32_t *src_ids, const int32_t *slots,
+                                           int n, void *stream);
+
+/*
  * Retained-support KL gate of Path B (Sec. "Online parameter update", Eq. 5 and the admission
  * rule; Algorithm 1, Path B).  For each of E verification events: support = the ids of the K
  * (paper: K_logit = 256; 1 <= K <= EVOSPEC_KL_K_MAX, K <= V) largest target logits, ties to the

@@ -48,6 +48,9 @@ def _load() -> ctypes.CDLL:
     L.evospec_active_gather.argtypes = [vp, ci, ci, vp, vp, ci, vp, vp, ci, vp]
     L.evospec_active_lmhead_topk.restype = ci
     L.evospec_active_lmhead_topk.argtypes = [vp, ci, ci, vp, vp, ci, ci, vp, vp, vp, vp, sz, vp]
+    L.evospec_active_lmhead_topk_then_update.restype = ci
+    L.evospec_active_lmhead_topk_then_update.argtypes = [vp, ci, ci, vp, vp, ci, ci, vp, vp, vp, vp, sz,
+                                                         vp, ci, vp, vp, ci, vp]
     L.evospec_active_lmhead_partials.restype = ci
     L.evospec_active_lmhead_partials.argtypes = [vp, ci, ci, vp, vp, ci, ci, vp, sz, vp]
     L.evospec_active_lmhead_merge.restype = ci
@@ -172,6 +175,26 @@ def active_lmhead_topk(h, W_act, ids, k, out_vals=None, out_ids=None, out_logz=N
                                           _ptr(out_vals), _ptr(out_ids), _ptr(out_logz),
                                           _ptr(workspace), workspace.numel(), _stream()),
            "evospec_active_lmhead_topk")
+    return out_vals, out_ids, out_logz
+
+
+def active_lmhead_topk_then_update(h, W_act, act_ids, k, W_lm, src_ids, slots, out_vals=None, out_ids=None,
+                                   out_logz=None, workspace=None):
+    """The head on W_act / act_ids as they are, then the update W_act[slots] <- W_lm[src_ids] (one launch
+    fewer than the two calls).  Returns (vals, ids, logz) of the head."""
+    import torch
+    M, d, V_act = _head_shapes(h, W_act, act_ids)
+    dev = h.device
+    out_vals = torch.empty((M, k), dtype=torch.float32, device=dev) if out_vals is None else out_vals
+    out_ids = torch.empty((M, k), dtype=torch.int32, device=dev) if out_ids is None else out_ids
+    out_logz = torch.empty((M,), dtype=torch.float32, device=dev) if out_logz is None else out_logz
+    if workspace is None:
+        workspace = _workspace(None, workspace_bytes(M, V_act, d, k), dev)
+    n = int(src_ids.numel())
+    _check(lib.evospec_active_lmhead_topk_then_update(
+        _ptr(h), M, d, _ptr(W_act), _ptr(act_ids), V_act, k, _ptr(out_vals), _ptr(out_ids), _ptr(out_logz),
+        _ptr(workspace), workspace.numel(), _ptr(W_lm), int(W_lm.shape[0]), _ptr(src_ids),
+        _ptr(slots) if slots is not None else None, n, _stream()), "evospec_active_lmhead_topk_then_update")
     return out_vals, out_ids, out_logz
 
 

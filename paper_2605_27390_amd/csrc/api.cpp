@@ -159,9 +159,13 @@ int evospec_active_lmhead_merge(int M, int V_act, int d, int k, float* out_vals,
     return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
 }
 
-int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, const int32_t* ids,
-                               int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
-                               void* workspace, size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// The head, with an optional update that rides on its last merge launch.
+int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids,
+              int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
+              void* workspace, size_t workspace_bytes, void* stream, const GatherArgs* update) {
     int rc = check_head_args(h, M, d, W_act, V_act, k);
     if (rc) return rc;
     if (M == 0) return EVOSPEC_OK;
@@ -182,7 +186,7 @@ int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, c
         if (e != hipSuccess) return hip_fail(e);
         MergeSet a{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len, true};
         MergeSet none{};
-        e = launch_merge(a, none, k, out_vals, out_ids, out_logz, 0, M, st);
+        e = launch_merge(a, none, k, out_vals, out_ids, out_logz, 0, M, st, update);
         return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
     }
     for (int m0 = 0; m0 < M; m0 += kMTile) {            // passes of 64 draft rows share the scratch
@@ -193,10 +197,40 @@ int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, c
         if (e != hipSuccess) return hip_fail(e);
         MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0, kMTile};
         MergeSet none{};
-        e = launch_merge(a, none, k, out_vals, out_ids, out_logz, m0, rows, st);
+        e = launch_merge(a, none, k, out_vals, out_ids, out_logz, m0, rows, st, m0 + kMTile >= M ? update : nullptr);
         if (e != hipSuccess) return hip_fail(e);
     }
     return EVOSPEC_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, const int32_t* ids,
+                               int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    return head_impl(h, M, d, W_act, ids, V_act, k, out_vals, out_ids, out_logz, workspace, workspace_bytes,
+                     stream, nullptr);
+}
+
+int evospec_active_lmhead_topk_then_update(const void* h, int M, int d, void* W_act, int32_t* act_ids,
+                                           int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
+                                           void* workspace, size_t workspace_bytes,
+                                           const void* W_lm, int V, const int32_t* src_ids, const int32_t* slots,
+                                           int n, void* stream) {
+    if (V <= 0 || n < 0) return EVOSPEC_BAD_SHAPE;
+    if (!slots && n > V_act) return EVOSPEC_BAD_SHAPE;
+    if (n > 0 && (!W_lm || !src_ids || !act_ids)) return EVOSPEC_NULL_POINTER;
+    if (n > 0 && !aligned16(W_lm)) return EVOSPEC_MISALIGNED;
+    if (M == 0 || n == 0) {                       // nothing to ride on, or nothing to carry
+        int rc = head_impl(h, M, d, W_act, act_ids, V_act, k, out_vals, out_ids, out_logz, workspace,
+                           workspace_bytes, stream, nullptr);
+        if (rc || n == 0) return rc;
+        return evospec_active_gather(W_lm, V, d, src_ids, slots, n, W_act, act_ids, V_act, stream);
+    }
+    const GatherArgs upd{W_lm, V, d / 8, src_ids, slots, n, W_act, act_ids, V_act};
+    return head_impl(h, M, d, W_act, act_ids, V_act, k, out_vals, out_ids, out_logz, workspace, workspace_bytes,
+                     stream, &upd);
 }
 
 int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void* W_core,

@@ -18,32 +18,33 @@ namespace evospec {
 
 // ---------------------------------------------------------------------------------------
 // Row insertion  W_act[slot] <- W_lm[id], act_ids[slot] <- id  (bit copy, 16 B per lane).
-// One workgroup per row, grid-stride over the n rows of the update.
-__global__ void __launch_bounds__(256)
-gather_rows_kernel(const uint4* __restrict__ W_lm, int V, int row_vec /* d/8 */,
-                   const int32_t* __restrict__ src_ids, const int32_t* __restrict__ slots, int n,
-                   uint4* __restrict__ W_act, int32_t* __restrict__ act_ids, int V_act) {
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const int32_t id = src_ids[i];
-        const int32_t s = slots ? slots[i] : i;
-        if (id < 0 || id >= V || s < 0 || s >= V_act) continue;     // uniform per workgroup
-        const uint4* src = W_lm + (size_t)id * row_vec;
-        uint4* dst = W_act + (size_t)s * row_vec;
-        for (int c0 = 0; c0 < row_vec; c0 += 4 * 256) {
-            uint4 v[4];
+// One workgroup (256 threads) per row.
+__device__ __forceinline__ void gather_one_row(const GatherArgs& g, int i) {
+    const int32_t id = g.src_ids[i];
+    const int32_t s = g.slots ? g.slots[i] : i;
+    if (id < 0 || id >= g.V || s < 0 || s >= g.V_act) return;      // uniform per workgroup
+    const uint4* src = static_cast<const uint4*>(g.W_lm) + (size_t)id * g.row_vec;
+    uint4* dst = static_cast<uint4*>(g.W_act) + (size_t)s * g.row_vec;
+    for (int c0 = 0; c0 < g.row_vec; c0 += 4 * 256) {
+        uint4 v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = c0 + u * 256 + threadIdx.x;
-                if (c < row_vec) v[u] = src[c];
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = c0 + u * 256 + threadIdx.x;
-                if (c < row_vec) dst[c] = v[u];
-            }
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * 256 + threadIdx.x;
+            if (c < g.row_vec) v[u] = src[c];
         }
-        if (threadIdx.x == 0) act_ids[s] = id;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * 256 + threadIdx.x;
+            if (c < g.row_vec) dst[c] = v[u];
+        }
     }
+    if (threadIdx.x == 0) g.act_ids[s] = id;
+}
+
+// grid-stride over the n rows of the update
+__global__ void __launch_bounds__(256)
+gather_rows_kernel(GatherArgs g) {
+    for (int i = blockIdx.x; i < g.n; i += gridDim.x) gather_one_row(g, i);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -430,7 +431,14 @@ __global__ void __launch_bounds__(kMergeThreads)
 lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_keys, size_t a_pass_stats,
                     size_t b_chunk_keys, size_t b_chunk_stats, int k, int pend_cap,
                     float* __restrict__ out_vals, int32_t* __restrict__ out_ids,
-                    float* __restrict__ out_logz) {
+                    float* __restrict__ out_logz, GatherArgs upd) {
+    // The blocks of grid row cb.n (present only when an update rides along) insert the rows of a
+    // dynamic-buffer update into the compact matrix: the partials that this launch merges were
+    // computed by an earlier launch, so nothing reads those rows any more.
+    if ((int)blockIdx.y == cb.n) {
+        if ((int)blockIdx.x < upd.n) gather_one_row(upd, blockIdx.x);
+        return;
+    }
     constexpr int NT = kMergeThreads;
     constexpr int NWV = NT / 64;
     __shared__ u64 run[2][kKMax];                    // running k best, descending
@@ -651,11 +659,13 @@ hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const 
 
 hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const MergeSet& b, size_t b_chunk_bytes,
                               const ChunkBatch& cb, int k, float* out_vals, int32_t* out_ids,
-                              float* out_logz, hipStream_t stream) {
+                              float* out_logz, hipStream_t stream, const GatherArgs* update) {
     if (cb.n < 1 || cb.n > kMaxChunks || a_pass_bytes % 8 != 0 || b_chunk_bytes % 8 != 0) return hipErrorInvalidValue;
     int max_rows = 0;
     for (int i = 0; i < cb.n; ++i) max_rows = cb.rows[i] > max_rows ? cb.rows[i] : max_rows;
-    if (max_rows == 0) return hipSuccess;
+    GatherArgs upd{};
+    if (update && update->n > 0) upd = *update;
+    if (max_rows == 0 && upd.n == 0) return hipSuccess;
     if ((a.list_len != 0 && (a.list_len < k || a.list_len > kKMax || (a.list_len & 15))) ||
         (b.list_len != 0 && (b.list_len < k || b.list_len > kKMax || (b.list_len & 15))))
         return hipErrorInvalidValue;
@@ -679,25 +689,25 @@ hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const Merg
     const PartialSet A = as_set(a), B = as_set(b);
     const int max_len = A.list_len > B.list_len ? A.list_len : B.list_len;
     const int pend_cap = k * max_len + k + 8;      // k qualifying lists in full, the running k (8-byte keys: < 34 KB)
-    hipLaunchKernelGGL(lmhead_merge_kernel, dim3(max_rows, cb.n), dim3(kMergeThreads), (size_t)pend_cap * 8, stream, A, B, cb,
-                       a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k, pend_cap,
-                       out_vals, out_ids, out_logz);
+    const int gx = max_rows > upd.n ? max_rows : upd.n;
+    hipLaunchKernelGGL(lmhead_merge_kernel, dim3(gx, cb.n + (upd.n > 0 ? 1 : 0)), dim3(kMergeThreads), (size_t)pend_cap * 8,
+                       stream, A, B, cb, a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k,
+                       pend_cap, out_vals, out_ids, out_logz, upd);
     return hipGetLastError();
 }
 
 hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
-                        float* out_logz, int out_row0, int nrows, hipStream_t stream) {
+                        float* out_logz, int out_row0, int nrows, hipStream_t stream, const GatherArgs* update) {
     ChunkBatch cb;
     cb.n = 1; cb.m0[0] = out_row0; cb.rows[0] = nrows; cb.seq[0] = 0; cb.a_pass[0] = 0; cb.a_slot[0] = 0;
-    return launch_merge_batch(a, 0, b, 0, cb, k, out_vals, out_ids, out_logz, stream);
+    return launch_merge_batch(a, 0, b, 0, cb, k, out_vals, out_ids, out_logz, stream, update);
 }
 
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
                          int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream) {
     const int grid = n < 8192 ? n : 8192;
-    hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(256), 0, stream,
-                       static_cast<const uint4*>(W_lm), V, d / 8, src_ids, slots, n,
-                       static_cast<uint4*>(W_act), act_ids, V_act);
+    const GatherArgs g{W_lm, V, d / 8, src_ids, slots, n, W_act, act_ids, V_act};
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(256), 0, stream, g);
     return hipGetLastError();
 }
 

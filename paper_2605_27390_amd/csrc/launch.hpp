@@ -33,10 +33,11 @@ hipError_t launch_partials_batch(const Plan& p, const void* h, const ChunkBatch&
                                  void* stats, hipStream_t stream);
 // One launch merges every chunk of the batch: row r of chunk i takes slot a_slot[i] + r of the first
 // set (moved by a_pass[i] * a_pass_bytes) and slot r of the second (moved by i * b_chunk_bytes), and
-// writes output row m0[i] + r.
+// writes output row m0[i] + r.  `update`, if given, is applied by extra blocks of the same launch (one
+// block per row).
 hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const MergeSet& b, size_t b_chunk_bytes,
                               const ChunkBatch& cb, int k, float* out_vals, int32_t* out_ids,
-                              float* out_logz, hipStream_t stream);
+                              float* out_logz, hipStream_t stream, const GatherArgs* update = nullptr);
 hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
                            const int32_t* ids, int V_act, int k, void* keys, void* stats,
                            hipStream_t stream);
@@ -45,7 +46,8 @@ hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const 
 hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, const int32_t* ids, int V_act,
                                 int k, void* keys, void* stats, hipStream_t stream);
 hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
-                        float* out_logz, int out_row0, int nrows, hipStream_t stream);
+                        float* out_logz, int out_row0, int nrows, hipStream_t stream,
+                        const GatherArgs* update = nullptr);
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
                          int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream);
 // Retained-support KL gate, one workgroup per event (K <= 256, d * 2 bytes <= 48 KB of LDS).

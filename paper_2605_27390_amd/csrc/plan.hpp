@@ -43,6 +43,19 @@ struct ChunkBatch {
     int a_slot[kMaxChunks];
 };
 
+// One dynamic-buffer update: n rows W_act[slots[i]] <- W_lm[src_ids[i]], act_ids[slots[i]] <- src_ids[i]
+// (slots == nullptr: slot i).  Device pointers; row_vec = d / 8.
+struct GatherArgs {
+    const void* W_lm = nullptr;
+    int V = 0, row_vec = 0;
+    const int32_t* src_ids = nullptr;
+    const int32_t* slots = nullptr;
+    int n = 0;
+    void* W_act = nullptr;
+    int32_t* act_ids = nullptr;
+    int V_act = 0;
+};
+
 struct Plan {
     int nw = 0, rgw = 0;     // wavefronts per workgroup, 16-row groups per wavefront
     int rc = 0;              // chunks in the W-operand ring

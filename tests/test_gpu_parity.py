@@ -335,3 +335,33 @@ def test_path_a_event_end_to_end(ev, oracle_mod):
     assert np.array_equal(act_ids.cpu().numpy()[:n_act], active)
     assert np.array_equal(bf16_dev_to_bits(W_act)[:n_act], W[active])
     assert len(res) == cap
+
+
+@pytest.mark.parametrize("M,n_new", [(20, 32), (64, 1), (70, 5), (130, 40), (5, 0)])
+def test_head_then_update_equals_the_two_calls(ev, M, n_new):
+    """The fused call must leave the outputs of the head on the old matrix and the matrix of the
+    separate gather, bit for bit."""
+    import torch
+    V, d, n_core, n_arc, k = 4000, 256, 700, 100, 10
+    W = gi.gen_W_lm(V, d)
+    ids = np.concatenate(gi.core_arc_ids(V, n_core, n_arc, seed=6))
+    h = to_dev_bf16(gi.gen_h(M, d, 40 + M))
+    Wd = to_dev_bf16(W)
+    mats = []
+    for _ in range(2):
+        W_act = torch.empty((ids.shape[0], d), dtype=torch.bfloat16, device="cuda")
+        act = torch.empty((ids.shape[0],), dtype=torch.int32, device="cuda")
+        ev.active_gather(Wd, to_dev_i32(ids), None, W_act, act)
+        mats.append((W_act, act))
+    slots, new_ids = gi.arc_update(V, ids, n_core, max(n_new, 1), seed=50 + M)
+    slots, new_ids = slots[:n_new], new_ids[:n_new]
+    sd, nd = to_dev_i32(slots), to_dev_i32(new_ids)
+    v0, i0, l0 = ev.active_lmhead_topk(h, mats[0][0], mats[0][1], k)
+    ev.active_gather(Wd, nd, sd, mats[0][0], mats[0][1])
+    v1, i1, l1 = ev.active_lmhead_topk_then_update(h, mats[1][0], mats[1][1], k, Wd, nd, sd)
+    torch.cuda.synchronize()
+    assert torch.equal(v0, v1) and torch.equal(i0, i1) and torch.equal(l0, l1)
+    assert torch.equal(mats[0][0].view(torch.int16), mats[1][0].view(torch.int16)) and torch.equal(mats[0][1], mats[1][1])
+    want = ids.copy(); want[slots] = new_ids
+    assert np.array_equal(mats[1][1].cpu().numpy(), want)
+    assert np.array_equal(bf16_dev_to_bits(mats[1][0]), W[want])
