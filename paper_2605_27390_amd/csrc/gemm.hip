@@ -4,8 +4,8 @@
 //
 // One workgroup of four wavefronts (one per SIMD) computes a 256 x 256 tile of z = W_act h^T
 // (256 active rows x 256 draft rows) over the whole hidden dimension.  Both operands travel
-// HBM/L2 -> LDS with direct-to-LDS loads (no staging registers) in chunks of 32 hidden elements
-// through a ring of four stages; every wavefront owns a 128 x 128 quadrant = 8 x 8 accumulators
+// HBM/L2 -> LDS with direct-to-LDS loads (no staging registers, whole 128-byte lines per request)
+// in chunks of 32 hidden elements through a ring of four stages, loaded two at a time; every wavefront owns a 128 x 128 quadrant = 8 x 8 accumulators
 // of v_mfma_f32_16x16x32_bf16, which fill the 256 accumulation registers of a lane, and reads
 // the operands of the next chunk from LDS while the matrix cores work on the current one.
 // The logits never leave the registers: each wavefront reduces its quadrant, per draft row, to
@@ -29,7 +29,6 @@ constexpr int kGStages = 4;                   // ring of LDS stages
 constexpr int kGOperandBytes = kGemmTile * kGK * 2;           // 16 KB: 256 rows x 64 B, no padding
 constexpr int kGStageBytes = 2 * kGOperandBytes;              // W_act rows, then h rows
 constexpr size_t kGLds = (size_t)kGStages * kGStageBytes;     // 128 KB
-constexpr int kGLoads = kGemmTile / 16 / 4;                   // direct-to-LDS loads per wavefront, operand and chunk
 constexpr int kGFastLen = 16;                 // list length the staged common path of the epilogue handles
 constexpr int kGEpiBytes = 16 * kGemmSlab * 8 + 64 * 32 * 4 + kGemmSlab * 4;   // per wavefront: lists, parked logits, ids
 static_assert(8 * 16 * kGFastLen * 8 + 64 * 8 <= 16 * kGemmSlab * 8 + 64 * 32 * 4, "staged lists and spare slots fit");
@@ -37,18 +36,18 @@ constexpr size_t kGLdsTotal = kGLds > 4ull * kGEpiBytes ? kGLds : 4ull * kGEpiBy
 
 static_assert(kGLds <= (size_t)kLdsLimit, "operand ring exceeds the LDS of a compute unit");
 static_assert(kGLdsTotal <= (size_t)kLdsLimit, "epilogue lists exceed the LDS of a compute unit");
-static_assert(kGLoads == 4, "four wavefronts share 16 blocks of 16 rows");
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// A row of a stage holds 32 hidden elements = four 16-byte pieces.  Piece p of row r sits in
-// slot p ^ swz(r).  The 16 lanes of an MFMA operand read take one piece of 16 consecutive rows:
+// A row of a chunk holds 32 hidden elements = four 16-byte pieces, rows are stored in blocks of 8
+// (see the kernel).  Piece p of row r sits in slot p ^ swz(r).  The 16 lanes of an MFMA operand read take one piece of 16 consecutive rows:
 // with this swizzle any 8 consecutive rows fall into 8 different 16-byte columns of a 128-byte
 // bank window and any 16 into 16 different columns of a 256-byte window, so the read is free of
-// bank conflicts for either bank count.  The direct-to-LDS load writes lane L of a wavefront to
-// byte 16 L of a 1 KB block (16 rows), so the swizzle is applied on the source side: the lane
-// that fills (row, slot) fetches piece slot ^ swz(row).
+// bank conflicts for either bank count (consecutive rows are 64 bytes apart inside a block, blocks
+// 1 KB apart).  The direct-to-LDS load writes lane L of a wavefront to byte 16 L of a 1 KB block, so
+// the swizzle is applied on the source side: the lane that fills (row, slot) fetches piece
+// slot ^ swz(row).
 __device__ __forceinline__ int swz(int row) { return (((row & 15) >> 1) + ((row & 15) >> 3)) & 3; }
 
 // Accumulators are pinned to the accumulation registers: with all 256 of them live, the
@@ -134,24 +133,29 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
     const int tile_v = logical / m_tiles, tile_m = logical - tile_v * m_tiles;
     const int v0 = tile_v * kGemmTile, m0 = tile_m * kGemmTile;
 
-    // direct-to-LDS loads of this wavefront: blocks of 16 rows number 4 w + i of either operand
-    const uint16_t* asrc[kGLoads];
-    const uint16_t* bsrc[kGLoads];
+    // Direct-to-LDS loads fetch whole 128-byte lines: one wave-level load takes, for 8 rows, the
+    // 64 bytes of an even chunk (lanes 0-31) and of the following odd chunk (lanes 32-63).  The
+    // ring therefore consists of 2 pair-stages of 64 KB; in a pair-stage, operand o, block b of 8
+    // rows: bytes [o * 32 KB + b * 1 KB, +1 KB) = [chunk parity][row][slot].
+    constexpr int kPairBytes = 2 * kGStageBytes;                   // 64 KB
+    constexpr int kPLoads = kGemmTile / 8 / 4;                     // 8 blocks of 8 rows per wavefront and operand
+    const uint16_t* asrc[kPLoads];
+    const uint16_t* bsrc[kPLoads];
 #pragma unroll
-    for (int i = 0; i < kGLoads; ++i) {
-        const int r = (4 * w + i) * 16 + (lane >> 2);
+    for (int i = 0; i < kPLoads; ++i) {
+        const int r = (kPLoads * w + i) * 8 + ((lane >> 2) & 7);
         const int piece = (lane & 3) ^ swz(r);
-        asrc[i] = W + (size_t)min(v0 + r, V_act - 1) * d + piece * 8;      // rows past the end repeat
-        bsrc[i] = h + (size_t)min(m0 + r, M - 1) * d + piece * 8;          // the last one, masked later
+        const int half = lane >> 5;
+        asrc[i] = W + (size_t)min(v0 + r, V_act - 1) * d + half * kGK + piece * 8;   // rows past the end repeat
+        bsrc[i] = h + (size_t)min(m0 + r, M - 1) * d + half * kGK + piece * 8;       // the last one, masked later
     }
-    const int nchunks = d / kGK;                                   // d is a multiple of kGK here
-    // Load number j (0..7) of chunk c: block i = j/2 of W_act rows (j even) or of h rows (j odd).
-    // Chunks past the end repeat the last one into a stage nobody reads again, which keeps the
-    // number of loads in flight, and with it every wait below, the same in every iteration.
-    auto issue_one = [&](int c, int j) {
-        const size_t koff = (size_t)min(c, nchunks - 1) * kGK;
-        unsigned char* dst = smem + (c & (kGStages - 1)) * kGStageBytes + (j & 1) * kGOperandBytes +
-                             (4 * w + (j >> 1)) * 1024;
+    const int nchunks = d / kGK;                                   // even: d is a multiple of 64 here
+    const int npairs = nchunks / 2;
+    // Load number j (0..15) of pair p: block j/2 of this wavefront's W_act rows (j even) or h rows (j odd).
+    // Pairs past the end repeat the last one into a stage nobody reads again.
+    auto issue_one = [&](int p, int j) {
+        const size_t koff = (size_t)min(p, npairs - 1) * (2 * kGK);
+        unsigned char* dst = smem + (p & 1) * kPairBytes + (j & 1) * (2 * kGOperandBytes) + (kPLoads * w + (j >> 1)) * 1024;
         const uint16_t* src = ((j & 1) ? bsrc[j >> 1] : asrc[j >> 1]) + koff;
         __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
     };
@@ -162,30 +166,32 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
 #pragma unroll
         for (int mb = 0; mb < 8; ++mb) acc[rg][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // operand reads: lane (n16, g) takes piece g of row n16 of each 16-row block of its quadrant
-    const int a_rd = (wv * 128 + n16) * (kGK * 2) + ((g ^ swz(n16)) * 16);
-    const int b_rd = kGOperandBytes + (wm * 128 + n16) * (kGK * 2) + ((g ^ swz(n16)) * 16);
+    // operand reads: lane (n16, g) takes piece g of row n16 of each 16-row block of its quadrant;
+    // row R of an operand sits in block R / 8 at row R % 8
+    auto row_off = [&](int R) { return (R >> 3) * 1024 + (R & 7) * 64; };
+    const int a_rd = row_off(wv * 128 + n16) + ((g ^ swz(n16)) * 16);
+    const int b_rd = 2 * kGOperandBytes + row_off(wm * 128 + n16) + ((g ^ swz(n16)) * 16);
     bf16x8 opa[2][8], opb[2][8];
+    auto stage_of = [&](int c) { return ((c >> 1) & 1) * kPairBytes + (c & 1) * 512; };
     auto read_a = [&](auto SET, int c, int i) {
-        opa[decltype(SET)::value][i] = *reinterpret_cast<const bf16x8*>(
-            smem + (c & (kGStages - 1)) * kGStageBytes + a_rd + i * 16 * (kGK * 2));
+        opa[decltype(SET)::value][i] = *reinterpret_cast<const bf16x8*>(smem + stage_of(c) + a_rd + i * 2048);
     };
     auto read_b = [&](auto SET, int c, int i) {
-        opb[decltype(SET)::value][i] = *reinterpret_cast<const bf16x8*>(
-            smem + (c & (kGStages - 1)) * kGStageBytes + b_rd + i * 16 * (kGK * 2));
+        opb[decltype(SET)::value][i] = *reinterpret_cast<const bf16x8*>(smem + stage_of(c) + b_rd + i * 2048);
     };
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, 1>;
 
     // One chunk: 64 MFMAs on the operands in registers (set CUR); in the gaps, the 16 operand
-    // reads of chunk c+1 (into set 1 - CUR) and the 8 loads of chunk c+4 (into the stage of
-    // chunk c, which every wavefront finished reading before the barrier).  At the top, chunks up
-    // to c+3 have been requested, in order, 8 loads each: chunk c+1 has landed once at most 16
-    // loads are outstanding.
+    // reads of chunk c+1 (into set 1 - CUR) and, in odd chunks, the 16 loads of the pair (c+3, c+4)
+    // into the pair-stage of chunks (c-1, c), which every wavefront finished reading before the
+    // barrier.  An odd chunk needs the pair (c+1, c+2), requested two chunks ago and the youngest
+    // request: wait for everything.  An even chunk needs its own pair, which its predecessor needed too.
     auto step = [&](auto CUR, int c) {
         constexpr int P = decltype(CUR)::value;
         using NXT = std::integral_constant<int, 1 - P>;
-        asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+        if (P == 1) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        else asm volatile("s_barrier" ::: "memory");
 #pragma unroll
         for (int rg = 0; rg < 8; ++rg) {
 #pragma unroll
@@ -196,27 +202,25 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
                 if (q & 1) read_a(NXT{}, c + 1, q >> 1);
                 else read_b(NXT{}, c + 1, q >> 1);
             }
-            issue_one(c + 4, rg);
+            if (P == 1) { issue_one((c + 3) >> 1, 2 * rg); issue_one((c + 3) >> 1, 2 * rg + 1); }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     };
 
 #pragma unroll
-    for (int c = 0; c < kGStages; ++c)
+    for (int p = 0; p < 2; ++p)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) issue_one(c, j);
-    // chunk 0 must have landed before its operands are read
-    asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+        for (int j = 0; j < 16; ++j) issue_one(p, j);
+    // pair 0 must have landed before its operands are read
+    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
 #pragma unroll
     for (int i = 0; i < 8; ++i) { read_b(S0{}, 0, i); read_a(S0{}, 0, i); }
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 7" ::: "memory");
 
-    int c = 0;
-    for (; c + 1 < nchunks; c += 2) {
+    for (int c = 0; c < nchunks; c += 2) {
         step(S0{}, c);
         step(S1{}, c + 1);
     }
-    if (c < nchunks) step(S0{}, c);
     // the last MFMAs drain before the accumulators are read; the ring is dead once the trailing
     // loads have landed and every wavefront is here
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -491,7 +495,7 @@ hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, cons
                                 int k, void* keys, void* stats, hipStream_t stream) {
     const int v_tiles = (V_act + kGemmTile - 1) / kGemmTile;
     const int m_tiles = (M + kGemmTile - 1) / kGemmTile;
-    if (d % kGK != 0 || d < kGK) return hipErrorInvalidValue;      // callers route such d elsewhere
+    if (d % (2 * kGK) != 0 || d < 2 * kGK) return hipErrorInvalidValue;      // callers route such d elsewhere
     auto kern = lmhead_gemm_kernel;
     constexpr int kMaxDevices = 64;
     static bool attr_set[kMaxDevices] = {};

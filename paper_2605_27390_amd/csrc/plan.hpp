@@ -129,8 +129,9 @@ inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, in
 constexpr int kGemmTile = 256;
 constexpr int kGemmSlab = 128;
 constexpr int kGemmMinRows = 129;
-constexpr int kGemmKChunk = 32;       // the large-M kernel needs d to be a multiple of this
-inline bool use_gemm(int M, int d) { return M >= kGemmMinRows && d % kGemmKChunk == 0; }
+constexpr int kGemmKChunk = 32;       // hidden elements per MFMA step; the large-M kernel loads two chunks at
+                                      // a time and needs d to be a multiple of 64
+inline bool use_gemm(int M, int d) { return M >= kGemmMinRows && d % (2 * kGemmKChunk) == 0; }
 
 // Key slots per (slab, draft row) list of the large-M path: the kernel leaves every logit that
 // reaches a lower bound of the slab's k-th best, unranked; rarely more than k + a few.

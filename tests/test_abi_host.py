@@ -47,7 +47,7 @@ def test_workspace_bytes(ev):
     assert 0 < a < b
     assert ev.workspace_bytes(60, 36864, 4096, 20) > a
     assert ev.workspace_bytes(128, 36864, 4096, 10) == a           # 64-row passes reuse the scratch
-    assert ev.workspace_bytes(960, 36864, 4104, 10) == a           # hidden size not a multiple of 32: passes
+    assert ev.workspace_bytes(960, 36864, 4104, 10) == a           # hidden size not a multiple of 64: passes
     # from 129 rows on one launch keeps a partial per 128 active rows and draft row
     big = ev.workspace_bytes(960, 36864, 4096, 10)
     assert big >= 288 * 960 * (10 * 8 + 8)

@@ -1,5 +1,5 @@
 """GPU parity of the large-M path (256 x 256 MFMA tiles, taken from 129 draft rows on when the
-hidden size is a multiple of 32) against the fp64 oracle.  Needs an MI355X: run with `-m gpu`."""
+hidden size is a multiple of 64) against the fp64 oracle.  Needs an MI355X: run with `-m gpu`."""
 import numpy as np
 import pytest
 
@@ -13,11 +13,11 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("M,V_act,d,k", [
     (129, 1000, 256, 10),      # one draft-row tile with a tail, 4 active-row tiles with a tail
     (256, 256, 64, 10),        # exactly one tile, two chunks
-    (257, 257, 32, 5),         # one row past a tile in both directions, a single chunk
-    (300, 100, 96, 10),        # second half of the only active-row tile wholly empty
+    (257, 257, 64, 5),         # one row past a tile in both directions, a single pair of chunks
+    (300, 100, 192, 10),       # second half of the only active-row tile wholly empty
     (300, 128, 128, 64),       # k above the group filter's range, exactly one slab
     (512, 777, 4096, 10),      # the benchmark's hidden size
-    (130, 40, 160, 33),        # fewer rows than a slab, k > 32
+    (130, 40, 320, 33),        # fewer rows than a slab, k > 32
     (200, 5, 64, 5),           # k == V_act
 ])
 def test_large_m_shapes(ev, oracle_mod, M, V_act, d, k):
@@ -32,7 +32,7 @@ def test_large_m_identity_ids_and_fallback_hidden_size(ev, oracle_mod):
     v, i, l = run_head(ev, h, W, None, 10)
     z = oracle_mod.logits(h, W)
     check_head(v, i, l, z, np.arange(600, dtype=np.int32), 10, "ids=None")
-    # a hidden size that is not a multiple of 32 takes the 64-row passes instead
+    # a hidden size that is not a multiple of 64 takes the 64-row passes instead
     W, h, ids = problem(42, 600, 264, 140)
     v, i, l = run_head(ev, h, W, ids, 10)
     check_head(v, i, l, oracle_mod.logits(h, W), ids, 10, "d=264")
@@ -42,7 +42,7 @@ def test_large_m_exact_small_integers(ev):
     """Operands whose products and sums are exact in fp32: logits must match exactly, which pins
     the operand layout of the tiles (row/column/hidden-index mapping) bit for bit."""
     rng = np.random.default_rng(5)
-    M, V_act, d, k = 261, 391, 96, 7
+    M, V_act, d, k = 261, 391, 128, 7
     Wf = rng.integers(-4, 5, size=(V_act, d)).astype(np.float32)
     hf = rng.integers(-4, 5, size=(M, d)).astype(np.float32)
     W, h = gi.f32_to_bf16_bits(Wf), gi.f32_to_bf16_bits(hf)
