@@ -18,23 +18,24 @@ namespace evospec {
 
 // ---------------------------------------------------------------------------------------
 // Row insertion  W_act[slot] <- W_lm[id], act_ids[slot] <- id  (bit copy, 16 B per lane).
-// One workgroup (256 threads) per row.
+// One workgroup per row.
 __device__ __forceinline__ void gather_one_row(const GatherArgs& g, int i) {
     const int32_t id = g.src_ids[i];
     const int32_t s = g.slots ? g.slots[i] : i;
     if (id < 0 || id >= g.V || s < 0 || s >= g.V_act) return;      // uniform per workgroup
     const uint4* src = static_cast<const uint4*>(g.W_lm) + (size_t)id * g.row_vec;
     uint4* dst = static_cast<uint4*>(g.W_act) + (size_t)s * g.row_vec;
-    for (int c0 = 0; c0 < g.row_vec; c0 += 4 * 256) {
+    const int nt = blockDim.x;
+    for (int c0 = 0; c0 < g.row_vec; c0 += 4 * nt) {
         uint4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int c = c0 + u * 256 + threadIdx.x;
+            const int c = c0 + u * nt + threadIdx.x;
             if (c < g.row_vec) v[u] = src[c];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int c = c0 + u * 256 + threadIdx.x;
+            const int c = c0 + u * nt + threadIdx.x;
             if (c < g.row_vec) dst[c] = v[u];
         }
     }
@@ -414,7 +415,6 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
 // batched variant).  Every slab's list is sorted, so its head is its maximum: per block of 256
 // lists the k-th largest head (together with the running result) bounds the answer from below,
 // at most k lists reach above that bound, and only their entries are ranked exactly.
-constexpr int kMergeThreads = 256;
 
 // An unranked list slot holds (logit bits << 32) | id; all ones = empty.
 __device__ __forceinline__ u64 pair_key(uint32_t zbits, uint32_t id) {
@@ -427,7 +427,8 @@ __device__ __forceinline__ u64 wave_bcast(u64 x, int src_lane /*uniform*/) {
     return ((u64)hi << 32) | lo;
 }
 
-__global__ void __launch_bounds__(kMergeThreads)
+template <int NT>
+__global__ void __launch_bounds__(NT)
 lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_keys, size_t a_pass_stats,
                     size_t b_chunk_keys, size_t b_chunk_stats, int k, int pend_cap,
                     float* __restrict__ out_vals, int32_t* __restrict__ out_ids,
@@ -439,7 +440,6 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
         if ((int)blockIdx.x < upd.n) gather_one_row(upd, blockIdx.x);
         return;
     }
-    constexpr int NT = kMergeThreads;
     constexpr int NWV = NT / 64;
     __shared__ u64 run[2][kKMax];                    // running k best, descending
     __shared__ u64 cand[(NWV + 1) * kKMax];          // per-wave best heads, then the running list
@@ -690,9 +690,17 @@ hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const Merg
     const int max_len = A.list_len > B.list_len ? A.list_len : B.list_len;
     const int pend_cap = k * max_len + k + 8;      // k qualifying lists in full, the running k (8-byte keys: < 34 KB)
     const int gx = max_rows > upd.n ? max_rows : upd.n;
-    hipLaunchKernelGGL(lmhead_merge_kernel, dim3(gx, cb.n + (upd.n > 0 ? 1 : 0)), dim3(kMergeThreads), (size_t)pend_cap * 8,
-                       stream, A, B, cb, a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k,
-                       pend_cap, out_vals, out_ids, out_logz, upd);
+    // enough threads to take all lists of a row in one round where possible (one list per thread and round)
+    const int total = A.n_slabs + B.n_slabs;
+    const dim3 grid(gx, cb.n + (upd.n > 0 ? 1 : 0));
+#define EVOSPEC_MERGE(NT_)                                                                                  \
+    hipLaunchKernelGGL(lmhead_merge_kernel<NT_>, grid, dim3(NT_), (size_t)pend_cap * 8, stream, A, B, cb,    \
+                       a_pass_bytes / 8, a_pass_bytes / 8, b_chunk_bytes / 8, b_chunk_bytes / 8, k, pend_cap, \
+                       out_vals, out_ids, out_logz, upd)
+    if (total <= 256) EVOSPEC_MERGE(256);
+    else if (total <= 512) EVOSPEC_MERGE(512);
+    else EVOSPEC_MERGE(1024);
+#undef EVOSPEC_MERGE
     return hipGetLastError();
 }
 
