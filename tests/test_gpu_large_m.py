@@ -70,3 +70,60 @@ def test_large_m_matches_row_passes(ev):
         np.testing.assert_allclose(l0[r0:r0 + 128], l1, rtol=1e-5)
         same = (i0[r0:r0 + 128] == i1).mean()
         assert same > 0.995, same
+
+
+def seg_check(ev, oracle_mod, V, d, S, n_core, n_arc, row_off, k, seed):
+    import torch
+    W = gi.gen_normal_bf16(V, d, seed, 0.05)
+    core, arcs = gi.batched_ids(V, max(n_core, 1), max(n_arc, 1), S, seed=seed + 1)
+    core, arcs = core[:n_core], arcs[:, :n_arc]
+    M = int(row_off[-1])
+    h = gi.gen_h(M, d, seed + 2)
+    W_core = to_dev_bf16(W[core]) if n_core else torch.empty((0, d), dtype=torch.bfloat16, device="cuda")
+    W_arc = to_dev_bf16(np.stack([W[arcs[s]] for s in range(S)])) if n_arc else \
+        torch.empty((S, 0, d), dtype=torch.bfloat16, device="cuda")
+    ids_arc = to_dev_i32(arcs) if n_arc else torch.empty((S, 0), dtype=torch.int32, device="cuda")
+    v, i, l = ev.active_lmhead_topk_segmented(to_dev_bf16(h), W_core, to_dev_i32(core) if n_core else None,
+                                              W_arc, ids_arc, row_off, k)
+    torch.cuda.synchronize()
+    v, i, l = v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy()
+    for s in range(S):
+        r0, r1 = row_off[s], row_off[s + 1]
+        if r1 > r0:
+            union = np.concatenate([core, arcs[s]])
+            check_head(v[r0:r1], i[r0:r1], l[r0:r1], oracle_mod.logits(h[r0:r1], W[union]), union, k, f"seq {s}")
+
+
+def test_segmented_large_m_many_short_sequences(ev, oracle_mod):
+    """More than 64 chunks (two batched launches), sequences of 0..9 rows, shared core on the large-M path."""
+    rng = np.random.default_rng(3)
+    lens = rng.integers(0, 10, size=90)
+    lens[5] = 70                                                  # one sequence longer than a chunk
+    row_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    assert row_off[-1] >= 129
+    seg_check(ev, oracle_mod, 9000, 128, 90, 1500, 130, row_off, 10, 21)
+
+
+def test_segmented_without_core_or_without_extensions(ev, oracle_mod):
+    row_off = np.array([0, 100, 180, 300], dtype=np.int32)
+    seg_check(ev, oracle_mod, 5000, 64, 3, 0, 400, row_off, 10, 31)           # extensions only
+    seg_check(ev, oracle_mod, 5000, 64, 3, 700, 0, row_off, 10, 41)           # shared core only (large-M path)
+    seg_check(ev, oracle_mod, 5000, 64, 3, 700, 0, np.array([0, 10, 40, 100], dtype=np.int32), 10, 51)   # passes
+    seg_check(ev, oracle_mod, 5000, 64, 3, 3, 5, row_off, 8, 61)              # k == union size
+
+
+@pytest.mark.parametrize("k", [16, 17, 40, 64])
+def test_large_m_k_range(ev, oracle_mod, k):
+    W, h, ids = problem(500 + k, 700, 128, 200)
+    v, i, l = run_head(ev, h, W, ids, k)
+    check_head(v, i, l, oracle_mod.logits(h, W), ids, k, f"k={k}")
+
+
+def test_large_m_all_equal_logits(ev):
+    """h = 0: every logit is 0, every list overflows; the k smallest ids must come out, exactly."""
+    W, h, ids = problem(9, 1000, 64, 150)
+    h[:] = 0
+    v, i, l = run_head(ev, h, W, ids, 10)
+    want = np.sort(ids)[:10]
+    assert np.all(i == want[None, :]) and np.all(v == 0)
+    np.testing.assert_allclose(l, np.log(1000.0), rtol=1e-6)
