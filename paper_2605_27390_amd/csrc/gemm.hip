@@ -5,12 +5,13 @@
 // One workgroup of four wavefronts (one per SIMD) computes a 256 x 256 tile of z = W_act h^T
 // (256 active rows x 256 draft rows) over the whole hidden dimension.  Both operands travel
 // HBM/L2 -> LDS with direct-to-LDS loads (no staging registers, whole 128-byte lines per request)
-// in chunks of 32 hidden elements through a ring of four stages, loaded two at a time; every wavefront owns a 128 x 128 quadrant = 8 x 8 accumulators
-// of v_mfma_f32_16x16x32_bf16, which fill the 256 accumulation registers of a lane, and reads
-// the operands of the next chunk from LDS while the matrix cores work on the current one.
-// The logits never leave the registers: each wavefront reduces its quadrant, per draft row, to
-// the same partial the streaming kernel leaves per slab (max, sum-exp, k best keys), for a
-// "slab" of its 128 rows.
+// in chunks of 32 hidden elements through a ring of four stages, filled two at a time.  Every
+// wavefront owns a 128 x 128 quadrant = 8 x 8 accumulators of v_mfma_f32_16x16x32_bf16, which
+// fill the 256 accumulation registers of a lane, and reads the operands of the next chunk from
+// LDS while the matrix cores work on the current one.  The logits never leave the registers:
+// each wavefront reduces its quadrant, per draft row, to a partial for a "slab" of its 128 rows:
+// (max, sum-exp) and the logits that can still be among the row's k best, unranked, as
+// (logit, id) pairs; the merge kernel ranks them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -41,8 +42,8 @@ typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 // A row of a chunk holds 32 hidden elements = four 16-byte pieces, rows are stored in blocks of 8
-// (see the kernel).  Piece p of row r sits in slot p ^ swz(r).  The 16 lanes of an MFMA operand read take one piece of 16 consecutive rows:
-// with this swizzle any 8 consecutive rows fall into 8 different 16-byte columns of a 128-byte
+// (see the kernel).  Piece p of row r sits in slot p ^ swz(r).  The 16 lanes of an MFMA operand
+// read take one piece of 16 consecutive rows: with this swizzle any 8 consecutive rows fall into 8 different 16-byte columns of a 128-byte
 // bank window and any 16 into 16 different columns of a 256-byte window, so the read is free of
 // bank conflicts for either bank count (consecutive rows are 64 bytes apart inside a block, blocks
 // 1 KB apart).  The direct-to-LDS load writes lane L of a wavefront to byte 16 L of a 1 KB block, so
