@@ -299,7 +299,8 @@ def main() -> int:
         z_t = torch.randn((E_kl, V), dtype=torch.float32, device=dev) * 2.0
         h_kl = dev_bf16(gi.gen_h(E_kl, d, gi.SEED_H + 70))
         kl_out = ev.kl_gate(z_t, h_kl, W_lm, 256, 1.0)
-        kl_us = timed(lambda i: ev.kl_gate(z_t, h_kl, W_lm, 256, 1.0, *kl_out), 30, warm=3)
+        ws_kl = torch.empty(ev.kl_gate_workspace_bytes(E_kl, V), dtype=torch.uint8, device=dev)
+        kl_us = timed(lambda i: ev.kl_gate(z_t, h_kl, W_lm, 256, 1.0, *kl_out, ws_kl), 30, warm=3)
         extra["kl_gate_60x256_us"] = round(kl_us, 1)
         del z_t
         if not args.no_cpu_baseline:

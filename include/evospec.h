@@ -157,12 +157,15 @@ int evospec_active_lmhead_topk_then_update(const void *h, int M, int d, void *W_
  *   z_target  dev fp32 [E, V]         h_draft  dev bf16 [E, d], 16-B aligned
  *   W_lm      dev bf16 [V, d], 16-B aligned, d % 8 == 0, d <= 24,576
  *   out_support dev int32 [E, K]; out_target_logits, out_draft_logits dev fp32 [E, K]; out_kl dev fp32 [E]
- * T > 0.  No workspace, no synchronisation; E == 0 is a no-op.
+ *   workspace dev, 16-B aligned, at least evospec_kl_gate_workspace_bytes(E, V) bytes, scratch
+ * T > 0.  No synchronisation; E == 0 is a no-op.
  */
 #define EVOSPEC_KL_K_MAX 256
+int evospec_kl_gate_workspace_bytes(int E, int V, size_t *out_bytes /*host*/);
 int evospec_kl_gate(const float *z_target, int E, int V, const void *h_draft, int d, const void *W_lm,
                     int K, float T, int32_t *out_support, float *out_target_logits,
-                    float *out_draft_logits, float *out_kl, void *stream);
+                    float *out_draft_logits, float *out_kl, void *workspace, size_t workspace_bytes,
+                    void *stream);
 
 /*
  * Debug aid: checks 0 <= ids[i] < V and that no id occurs twice (Eq. 3 is a set).

@@ -23,5 +23,6 @@ from .binding import (  # noqa: F401
     active_lmhead_topk_segmented,
     validate_ids,
     kl_gate,
+    kl_gate_workspace_bytes,
 )
 from .arc import ArcManager, form_candidates, path_a_event, path_a_workspace_bytes  # noqa: F401,E402

@@ -60,7 +60,9 @@ def _load() -> ctypes.CDLL:
                                                        ctypes.POINTER(ctypes.c_int32), ci, ci,
                                                        vp, vp, vp, vp, sz, vp]
     L.evospec_kl_gate.restype = ci
-    L.evospec_kl_gate.argtypes = [vp, ci, ci, vp, ci, vp, ci, ctypes.c_float, vp, vp, vp, vp, vp]
+    L.evospec_kl_gate.argtypes = [vp, ci, ci, vp, ci, vp, ci, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
+    L.evospec_kl_gate_workspace_bytes.restype = ci
+    L.evospec_kl_gate_workspace_bytes.argtypes = [ci, ci, ctypes.POINTER(sz)]
     L.evospec_validate_ids.restype = ci
     L.evospec_validate_ids.argtypes = [vp, ci, ci, vp]
     return L
@@ -250,7 +252,14 @@ def validate_ids(ids, V: int) -> bool:
     return True
 
 
-def kl_gate(z_target, h_draft, W_lm, K=256, T=1.0, out_support=None, out_zt=None, out_zq=None, out_kl=None):
+def kl_gate_workspace_bytes(E, V):
+    out = ctypes.c_size_t(0)
+    _check(lib.evospec_kl_gate_workspace_bytes(int(E), int(V), ctypes.byref(out)), "evospec_kl_gate_workspace_bytes")
+    return int(out.value)
+
+
+def kl_gate(z_target, h_draft, W_lm, K=256, T=1.0, out_support=None, out_zt=None, out_zq=None, out_kl=None,
+            workspace=None):
     """Retained-support KL gate (Path B): returns (support int32 [E,K], target logits, draft logits
     fp32 [E,K], kl fp32 [E]).  z_target fp32 [E,V], h_draft bf16 [E,d], W_lm bf16 [V,d], all on the GPU."""
     import torch
@@ -263,7 +272,10 @@ def kl_gate(z_target, h_draft, W_lm, K=256, T=1.0, out_support=None, out_zt=None
         out_zt = torch.empty((E, K), dtype=torch.float32, device=dev)
         out_zq = torch.empty((E, K), dtype=torch.float32, device=dev)
         out_kl = torch.empty((E,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(kl_gate_workspace_bytes(E, V), dtype=torch.uint8, device=dev)
     _check(lib.evospec_kl_gate(z_target.data_ptr(), int(E), int(V), h_draft.data_ptr(), int(d), W_lm.data_ptr(),
                                int(K), float(T), out_support.data_ptr(), out_zt.data_ptr(), out_zq.data_ptr(),
-                               out_kl.data_ptr(), torch.cuda.current_stream().cuda_stream), "evospec_kl_gate")
+                               out_kl.data_ptr(), workspace.data_ptr(), int(workspace.numel()),
+                               torch.cuda.current_stream().cuda_stream), "evospec_kl_gate")
     return out_support, out_zt, out_zq, out_kl

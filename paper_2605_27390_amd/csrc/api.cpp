@@ -332,17 +332,27 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
     return flush();
 }
 
+int evospec_kl_gate_workspace_bytes(int E, int V, size_t* out_bytes) {
+    if (!out_bytes) return EVOSPEC_NULL_POINTER;
+    if (E < 0 || V <= 0) return EVOSPEC_BAD_SHAPE;
+    *out_bytes = kl_gate_workspace_bytes(E > 0 ? E : 1, V);
+    return EVOSPEC_OK;
+}
+
 int evospec_kl_gate(const float* z_target, int E, int V, const void* h_draft, int d, const void* W_lm,
                     int K, float T, int32_t* out_support, float* out_target_logits,
-                    float* out_draft_logits, float* out_kl, void* stream) {
+                    float* out_draft_logits, float* out_kl, void* workspace, size_t workspace_bytes,
+                    void* stream) {
     if (E < 0 || V <= 0 || d <= 0 || (d % 8) != 0 || d > 24576 || !(T > 0.f)) return EVOSPEC_BAD_SHAPE;
     if (K < 1 || K > EVOSPEC_KL_K_MAX || K > V) return EVOSPEC_BAD_K;
     if (E == 0) return EVOSPEC_OK;
-    if (!z_target || !h_draft || !W_lm || !out_support || !out_target_logits || !out_draft_logits || !out_kl)
+    if (!z_target || !h_draft || !W_lm || !out_support || !out_target_logits || !out_draft_logits || !out_kl ||
+        !workspace)
         return EVOSPEC_NULL_POINTER;
-    if (!aligned16(h_draft) || !aligned16(W_lm)) return EVOSPEC_MISALIGNED;
+    if (!aligned16(h_draft) || !aligned16(W_lm) || !aligned16(workspace)) return EVOSPEC_MISALIGNED;
+    if (workspace_bytes < kl_gate_workspace_bytes(E, V)) return EVOSPEC_WORKSPACE_TOO_SMALL;
     hipError_t e = launch_kl_gate(z_target, E, V, h_draft, d, W_lm, K, T, out_support, out_target_logits,
-                                  out_draft_logits, out_kl, static_cast<hipStream_t>(stream));
+                                  out_draft_logits, out_kl, workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
 }
 

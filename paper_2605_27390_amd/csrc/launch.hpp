@@ -50,10 +50,11 @@ hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_
                         const GatherArgs* update = nullptr);
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
                          int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream);
-// Retained-support KL gate, one workgroup per event (K <= 256, d * 2 bytes <= 48 KB of LDS).
+// Retained-support KL gate (K <= 256, d * 2 bytes <= 48 KB of LDS); workspace of kl_gate_workspace_bytes.
+size_t kl_gate_workspace_bytes(int E, int V);
 hipError_t launch_kl_gate(const float* z_target, int E, int V, const void* h_draft, int d, const void* W_lm,
                           int K, float T, int32_t* out_support, float* out_zt, float* out_zq, float* out_kl,
-                          hipStream_t stream);
+                          void* workspace, hipStream_t stream);
 hipError_t run_validate_ids(const int32_t* ids, int n, int V, hipStream_t stream, int* bad);
 
 }  // namespace evospec
