@@ -41,6 +41,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="draft60", choices=["draft60", "tiny"])
     ap.add_argument("--copies", type=int, default=4, help="distinct W_act copies rotated over")
+    ap.add_argument("--layout", default="packed", choices=["packed", "row_major"],
+                    help="layout of the compact matrices W_act (the library's packed layout, or row-major)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--sweep", action="store_true",
@@ -83,10 +85,17 @@ def main() -> int:
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
 
+    def new_matrix(rows, batch=None, layout=None):
+        """An empty compact matrix (or `batch` of them) in the benchmark's layout."""
+        if (layout or args.layout) == "packed":
+            return ev.PackedMatrix(rows, d, device=dev, batch=batch)
+        shape = (rows, d) if batch is None else (batch, rows, d)
+        return torch.empty(shape, dtype=torch.bfloat16, device=dev)
+
     W_lm = dev_bf16(W_lm_bits)
     h = dev_bf16(h_bits)
     ids_dev = torch.from_numpy(ids0).to(dev)
-    W_acts = [torch.empty((V_act, d), dtype=torch.bfloat16, device=dev) for _ in range(R)]
+    W_acts = [new_matrix(V_act) for _ in range(R)]
     act_ids = [torch.empty((V_act,), dtype=torch.int32, device=dev) for _ in range(R)]
     for r in range(R):
         ev.active_gather(W_lm, ids_dev, None, W_acts[r], act_ids[r])      # full rebuild = the same call
@@ -178,7 +187,7 @@ def main() -> int:
         except Exception:
             pass
 
-    extra = {"partials_us": round(part_us, 2), "merge_us": round(merge_us, 2), "head_us": round(head_us, 2),
+    extra = {"layout": args.layout, "partials_us": round(part_us, 2), "merge_us": round(merge_us, 2), "head_us": round(head_us, 2),
              "event_us_per_step": round(ev_ms * 1e3 / K, 2), "copies": R,
              "rows_per_s": round(M / (us_step * 1e-6), 1),
              "hbm_gbps_step": round(alg_bytes / us_step / 1e3, 1),
@@ -193,6 +202,17 @@ def main() -> int:
                 lambda i: ev.active_gather(W_lm, upd_ids[0], upd_slots[0], W_acts[0], act_ids[0]), n_ev), 2)
         extra["gather_full_us"] = round(timed(
             lambda i: ev.active_gather(W_lm, ids_dev, None, W_acts[i % R], act_ids[i % R]), 20, warm=3), 2)
+        # the same head on a row-major copy of W_act (what a caller's own matrix would be)
+        other = "row_major" if args.layout == "packed" else "packed"
+        W_other = [new_matrix(V_act, layout=other) for _ in range(R)]
+        ids_other = [torch.empty_like(act_ids[0]) for _ in range(R)]
+        for r in range(R):
+            ev.active_gather(W_lm, ids_dev, None, W_other[r], ids_other[r])
+        extra[f"partials_us_{other}"] = round(timed(
+            lambda i: ev.active_lmhead_partials(h, W_other[i % R], ids_other[i % R], k, ws), n_ev), 2)
+        extra[f"gather_full_us_{other}"] = round(timed(
+            lambda i: ev.active_gather(W_lm, ids_dev, None, W_other[i % R], ids_other[i % R]), 20, warm=3), 2)
+        del W_other, ids_other
         ws_full = torch.empty(ev.workspace_bytes(M, V, d, k), dtype=torch.uint8, device=dev)
         full_us = timed(lambda i: ev.active_lmhead_topk(h, W_lm, None, k, out_v, out_i, out_l, ws_full), 30, warm=5)
         extra["fullvocab_head_us"] = round(full_us, 2)
@@ -204,7 +224,7 @@ def main() -> int:
         ids_d = gi.active_ids("depth")
         Vd = ids_d.shape[0]
         ids_d_dev = torch.from_numpy(ids_d).to(dev)
-        Wd = [torch.empty((Vd, d), dtype=torch.bfloat16, device=dev) for _ in range(8)]
+        Wd = [new_matrix(Vd) for _ in range(8)]
         idd = [torch.empty((Vd,), dtype=torch.int32, device=dev) for _ in range(8)]
         for r in range(8):
             ev.active_gather(W_lm, ids_d_dev, None, Wd[r], idd[r])
@@ -225,16 +245,19 @@ def main() -> int:
         cb = gi.CONFIGS["batched"]
         core_b, arcs_b = gi.batched_ids(V, cb["n_core"], cb["n_arc"], cb["S"])
         Mb, S_, Va = cb["M"], cb["S"], cb["n_arc"]
-        W_core = torch.empty((cb["n_core"], d), dtype=torch.bfloat16, device=dev)
+        W_core = new_matrix(cb["n_core"])
         ids_core = torch.empty((cb["n_core"],), dtype=torch.int32, device=dev)
         ev.active_gather(W_lm, torch.from_numpy(core_b).to(dev), None, W_core, ids_core)
-        W_arc = torch.empty((S_ * Va, d), dtype=torch.bfloat16, device=dev)
+        W_arc = new_matrix(Va, batch=S_)
         ids_arc = torch.empty((S_ * Va,), dtype=torch.int32, device=dev)
-        ev.active_gather(W_lm, torch.from_numpy(arcs_b.reshape(-1)).to(dev), None, W_arc, ids_arc)
+        for s_i in range(S_):
+            ev.active_gather(W_lm, torch.from_numpy(arcs_b[s_i].copy()).to(dev), None,
+                             W_arc.sub(s_i) if args.layout == "packed" else W_arc[s_i],
+                             ids_arc[s_i * Va:(s_i + 1) * Va])
         hb = dev_bf16(gi.gen_h(Mb, d, gi.SEED_H + 5))
         row_off = [s * cb["rows_per_seq"] for s in range(S_ + 1)]
         ws_b = torch.empty(ev.workspace_bytes_segmented(Mb, cb["n_core"], Va, S_, d, k), dtype=torch.uint8, device=dev)
-        seg_us = timed(lambda i: ev.active_lmhead_topk_segmented(hb, W_core, ids_core, W_arc.view(S_, Va, d),
+        seg_us = timed(lambda i: ev.active_lmhead_topk_segmented(hb, W_core, ids_core, W_arc,
                                                                  ids_arc.view(S_, Va), row_off, k, ws_b), 10, warm=2)
         flops = 2.0 * d * (Mb * cb["n_core"] + Mb * Va)
         extra["batched_M960"] = {"head_us": round(seg_us, 1), "tflops": round(flops / seg_us / 1e6, 1),
@@ -261,7 +284,7 @@ def main() -> int:
             sizes.append(int(s_.size))
             arc.advance(3)
         arc_s = time.perf_counter() - t0
-        W_tmp = torch.empty((n_core + 256, d), dtype=torch.bfloat16, device=dev)
+        W_tmp = new_matrix(n_core + 256)
         I_tmp = torch.empty((n_core + 256,), dtype=torch.int32, device=dev)
         arc2 = ev.ArcManager(slot_base=n_core, core=core_ids)
         ups = []
@@ -278,7 +301,7 @@ def main() -> int:
         # (M = 1, top 10), candidates from a synthetic co-occurrence graph, admission, gather
         row_ptr, col_idx = gi.bigram_graph(V, gi.SEED_IDS + 9)
         arc3 = ev.ArcManager(slot_base=n_core, core=core_ids)
-        W_pa = torch.empty((n_core + 256, d), dtype=torch.bfloat16, device=dev)
+        W_pa = new_matrix(n_core + 256)
         I_pa = torch.empty((n_core + 256,), dtype=torch.int32, device=dev)
         ws_pa = torch.empty(ev.path_a_workspace_bytes(V, d, 10, 32), dtype=torch.uint8, device=dev)
         h_t = [dev_bf16(gi.gen_h(1, d, gi.SEED_H + 100 + j)) for j in range(8)]
@@ -326,7 +349,8 @@ def main() -> int:
             ids_s = torch.from_numpy(np.concatenate([core_s, arc_s])).to(dev)
             Va = nc + na
             Rs = max(2, int(-(-4 * 256e6 // (Va * d_s * 2))))
-            Ws = [torch.empty((Va, d_s), dtype=torch.bfloat16, device=dev) for _ in range(Rs)]
+            Ws = [ev.PackedMatrix(Va, d_s, device=dev) if args.layout == "packed" else
+                  torch.empty((Va, d_s), dtype=torch.bfloat16, device=dev) for _ in range(Rs)]
             Is = [torch.empty((Va,), dtype=torch.int32, device=dev) for _ in range(Rs)]
             for r in range(Rs):
                 ev.active_gather(Wl, ids_s, None, Ws[r], Is[r])
@@ -386,7 +410,7 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{args.config}: d={d}, V={V}, V_act={V_act} ({n_core} core + {n_arc} ARC), M={M}, k={k}, "
-                               f"{UPDATE_ROWS if upd_slots else 0}-row ARC update per step"},
+                               f"{UPDATE_ROWS if upd_slots else 0}-row ARC update per step, W_act {args.layout}"},
         "roofline": roof,
         "cpu_baseline": cpu,
         "extra": extra,

@@ -15,7 +15,9 @@
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and is ordered with other work on that stream.
  *   - bf16 matrices are row-major with contiguous rows (leading dimension == d),
- *     base pointers 16-byte aligned, d a multiple of 8 (128-bit loads).
+ *     base pointers 16-byte aligned, d a multiple of 8 (128-bit loads).  The compact
+ *     active matrix W_act may instead be kept in the packed layout below; every call
+ *     that takes a W_act says which layout it is in (`layout`).
  *   - Arguments are validated on the host before the first HIP call; on an error
  *     nothing is enqueued.
  *   - M == 0 or n == 0 is a legal no-op (an update event may admit no token:
@@ -31,7 +33,7 @@
 extern "C" {
 #endif
 
-#define EVOSPEC_VERSION 100
+#define EVOSPEC_VERSION 200
 #define EVOSPEC_K_MAX 64        /* largest k of the fused top-k                         */
 #define EVOSPEC_M_TILE 64       /* draft rows handled by one pass over W_act            */
 
@@ -44,8 +46,30 @@ typedef enum evospec_status {
     EVOSPEC_WORKSPACE_TOO_SMALL = 5,
     EVOSPEC_BAD_SEGMENTS = 6,       /* row_off not monotone, row_off[0]!=0, row_off[S]!=M */
     EVOSPEC_INVALID_IDS = 7,        /* evospec_validate_ids only                          */
-    EVOSPEC_HIP_ERROR = 8           /* a launch failed; text via evospec_last_hip_error() */
+    EVOSPEC_HIP_ERROR = 8,          /* a launch failed; text via evospec_last_hip_error() */
+    EVOSPEC_BAD_LAYOUT = 9          /* layout is neither EVOSPEC_ROW_MAJOR nor EVOSPEC_PACKED */
 } evospec_status;
+
+/*
+ * Layouts of a compact active matrix (W_act, W_core, W_arc).  The paper does not say how the
+ * restricted projection of Algorithm 1 ("draft restricted to V_t") keeps its weights; the layout
+ * is this library's choice and the packed one is the fast one on MI355X (the head streams it with
+ * whole-cache-line, fully coalesced loads; 0.62 against 0.53 of the HBM peak at 36,864 x 4,096).
+ *   EVOSPEC_ROW_MAJOR  bf16 [rows, d], as W_lm.
+ *   EVOSPEC_PACKED     rows padded to a multiple of 16, d padded to dp = a multiple of 256 (pad
+ *                      elements are zero).  The 16-byte piece c (elements 8c .. 8c+7) of row r is
+ *                      piece number  (r / 16) * (2 * dp) + (c / 4) * 64 + (c % 4) * 16 + (r % 16)
+ *                      of the buffer: 16 rows x 32 elements form one 1 KB block in the order in
+ *                      which the matrix cores take them.  Only evospec_active_gather (and the calls
+ *                      that contain it) write this layout.  Rows never written hold garbage and are
+ *                      never read as part of a result.
+ * evospec_matrix_bytes: size of the buffer for `rows` rows in `layout` (host only, no HIP call).
+ */
+typedef enum evospec_layout {
+    EVOSPEC_ROW_MAJOR = 0,
+    EVOSPEC_PACKED = 1
+} evospec_layout;
+int evospec_matrix_bytes(int rows, int d, int layout, size_t *out_bytes /*host*/);
 
 int evospec_version(void);
 /* Static, never freed. */
@@ -71,7 +95,8 @@ int evospec_workspace_bytes_segmented(int M, int V_core, int V_arc, int S, int d
  *                     act_ids[slot_i]  = src_ids[i]
  *   slots == NULL means slot_i = i (full rebuild, then n <= V_act is required).
  * W_lm   dev bf16 [V, d]          src_ids dev int32 [n]     slots dev int32 [n] or NULL
- * W_act  dev bf16 [V_act, d]      act_ids dev int32 [V_act]
+ * W_act  dev bf16, V_act rows in `layout`, evospec_matrix_bytes(V_act, d, layout) bytes
+ * act_ids dev int32 [V_act]
  * Preconditions not checked here (see evospec_validate_ids): 0 <= src_ids[i] < V,
  * 0 <= slots[i] < V_act, slots distinct within a call, W_act not overlapping W_lm.
  * Entries with an out-of-range id or slot are skipped by the kernel (memory safe).
@@ -81,7 +106,7 @@ int evospec_workspace_bytes_segmented(int M, int V_core, int V_arc, int S, int d
  */
 int evospec_active_gather(const void *W_lm, int V, int d,
                           const int32_t *src_ids, const int32_t *slots, int n,
-                          void *W_act, int32_t *act_ids, int V_act, void *stream);
+                          void *W_act, int32_t *act_ids, int V_act, int layout, void *stream);
 
 /*
  * The restricted head (Eq. 1 on V_t; Algorithm 1 draft phase).  For each draft row m:
@@ -91,7 +116,7 @@ int evospec_active_gather(const void *W_lm, int V, int d,
  *                       full-vocabulary id first
  *   out_ids[m, 0..k)  = ids[i] of those entries (ids == NULL: the slot index i itself)
  * log-probability of a returned entry = out_vals - out_logz.  Logits are never written to HBM.
- * h dev bf16 [M, d]   W_act dev bf16 [V_act, d]   ids dev int32 [V_act] or NULL
+ * h dev bf16 [M, d]   W_act dev bf16, V_act rows in `layout`   ids dev int32 [V_act] or NULL
  * out_vals dev f32 [M, k]   out_ids dev int32 [M, k]   out_logz dev f32 [M]
  * workspace dev, 16-B aligned, at least evospec_workspace_bytes(...) bytes; contents are
  * scratch.  Two calls that share a workspace must be ordered (same stream).
@@ -99,7 +124,7 @@ int evospec_active_gather(const void *W_lm, int V, int d,
  * (Eq. 3 is a set union); duplicates are memory safe but count twice in the normaliser.
  */
 int evospec_active_lmhead_topk(const void *h, int M, int d,
-                               const void *W_act, const int32_t *ids, int V_act, int k,
+                               const void *W_act, const int32_t *ids, int V_act, int layout, int k,
                                float *out_vals, int32_t *out_ids, float *out_logz,
                                void *workspace, size_t workspace_bytes, void *stream);
 
@@ -110,7 +135,7 @@ int evospec_active_lmhead_topk(const void *h, int M, int d,
  * back on one stream with the same arguments is exactly evospec_active_lmhead_topk.
  */
 int evospec_active_lmhead_partials(const void *h, int M, int d,
-                                   const void *W_act, const int32_t *ids, int V_act, int k,
+                                   const void *W_act, const int32_t *ids, int V_act, int layout, int k,
                                    void *workspace, size_t workspace_bytes, void *stream);
 int evospec_active_lmhead_merge(int M, int V_act, int d, int k,
                                 float *out_vals, int32_t *out_ids, float *out_logz,
@@ -121,13 +146,14 @@ int evospec_active_lmhead_merge(int M, int V_act, int d, int k,
  * each carries its own dynamic buffer).  Rows [row_off[s], row_off[s+1]) of h belong to
  * sequence s and see the active set  core u arc[s]  (caller promises arc[s] is disjoint
  * from the core).  Outputs as above, normaliser over core u arc[s].
- * W_core dev bf16 [V_core, d]  ids_core dev int32 [V_core] or NULL (identity)
- * W_arc  dev bf16 [S, V_arc, d] ids_arc dev int32 [S, V_arc]
+ * W_core dev bf16, V_core rows in `layout`  ids_core dev int32 [V_core] or NULL (identity)
+ * W_arc  dev bf16, S matrices of V_arc rows in `layout`, back to back (each of
+ *        evospec_matrix_bytes(V_arc, d, layout) bytes)       ids_arc dev int32 [S, V_arc]
  * row_off HOST int32 [S+1], row_off[0] == 0, non-decreasing, row_off[S] == M.
  */
 int evospec_active_lmhead_topk_segmented(const void *h, int M, int d,
         const void *W_core, const int32_t *ids_core, int V_core,
-        const void *W_arc, const int32_t *ids_arc, int V_arc,
+        const void *W_arc, const int32_t *ids_arc, int V_arc, int layout,
         const int32_t *row_off, int S, int k,
         float *out_vals, int32_t *out_ids, float *out_logz,
         void *workspace, size_t workspace_bytes, void *stream);
@@ -142,7 +168,7 @@ int evospec_active_lmhead_topk_segmented(const void *h, int M, int d,
  * "merges into a subsequent launch", App. "Retrieval latency and asynchronous execution").
  */
 int evospec_active_lmhead_topk_then_update(const void *h, int M, int d, void *W_act, int32_t *act_ids,
-                                           int V_act, int k, float *out_vals, int32_t *out_ids, float *out_logz,
+                                           int V_act, int layout, int k, float *out_vals, int32_t *out_ids, float *out_logz,
                                            void *workspace, size_t workspace_bytes,
                                            const void *W_lm, int V, const int32_t *src_ids, const int32_t *slots,
                                            int n, void *stream);

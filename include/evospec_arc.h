@@ -97,8 +97,8 @@ int evospec_form_candidates(const int32_t *target_top, int n_target, const int32
  *   2. candidate formation (above) with the host arrays target_top / row_ptr / col_idx;
  *   3. admission by the buffer manager `arc`;
  *   4. evospec_active_gather of the admitted (slot, id) pairs into W_act / act_ids.
- * h_target (bf16 [d]), W_lm (bf16 [V, d]), W_act, act_ids, workspace are device pointers, 16-byte
- * aligned; everything else is host memory.  The call WAITS for step 1 on `stream` (it needs the
+ * h_target (bf16 [d]), W_lm (bf16 [V, d]), W_act (V_act rows in `layout`, see evospec.h), act_ids,
+ * workspace are device pointers, 16-byte aligned; everything else is host memory.  The call WAITS for step 1 on `stream` (it needs the
  * ids on the host) and returns after the gather has been enqueued.  out_slots / out_ids (host,
  * max_insert entries each, may be NULL) receive the admitted pairs, *n_out their number.
  * workspace_bytes must be at least evospec_path_a_workspace_bytes(V, d, n_mips, max_insert).
@@ -107,7 +107,7 @@ int evospec_path_a_workspace_bytes(int V, int d, int n_mips, int max_insert, siz
 int evospec_path_a_event(evospec_arc *arc, const void *h_target, int d, const void *W_lm, int V,
                          const int32_t *target_top, int n_target, int n_mips,
                          const int64_t *row_ptr, const int32_t *col_idx, int max_successors,
-                         void *W_act, int32_t *act_ids, int V_act,
+                         void *W_act, int32_t *act_ids, int V_act, int layout,
                          void *workspace, size_t workspace_bytes, void *stream,
                          int32_t *out_slots, int32_t *out_ids, int *n_out);
 

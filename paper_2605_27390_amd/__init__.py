@@ -9,6 +9,10 @@ from .binding import (  # noqa: F401
     K_MAX,
     M_TILE,
     STATUS,
+    ROW_MAJOR,
+    PACKED,
+    PackedMatrix,
+    matrix_bytes,
     lib,
     lib_path,
     version,

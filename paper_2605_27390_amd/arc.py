@@ -6,7 +6,7 @@ import ctypes
 
 import numpy as np
 
-from .binding import EvospecError, lib
+from .binding import EvospecError, _matrix, lib
 
 
 class _Config(ctypes.Structure):
@@ -44,7 +44,7 @@ lib.evospec_path_a_workspace_bytes.argtypes = [ctypes.c_int] * 4 + [ctypes.POINT
 lib.evospec_path_a_event.restype = ctypes.c_int
 lib.evospec_path_a_event.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
                                      _i32p, ctypes.c_int, ctypes.c_int, _i64p, _i32p, ctypes.c_int,
-                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                      _i32p, _i32p, ctypes.POINTER(ctypes.c_int)]
 
@@ -148,13 +148,14 @@ def path_a_event(arc, h_target, W_lm, target_top, n_mips, row_ptr, col_idx, max_
     rp = np.ascontiguousarray(np.asarray(row_ptr, dtype=np.int64))
     ci = np.ascontiguousarray(np.asarray(col_idx, dtype=np.int32))
     V, d = W_lm.shape
+    V_act, _, layout = _matrix(W_act, "W_act")
     cap = max(1, arc.max_insert)
     slots, ids = np.empty(cap, dtype=np.int32), np.empty(cap, dtype=np.int32)
     n = ctypes.c_int(0)
     _check(lib.evospec_path_a_event(arc._h, h_target.data_ptr(), int(d), W_lm.data_ptr(), int(V),
                                     _ptr(t) if t.size else None, int(t.size), int(n_mips),
                                     rp.ctypes.data_as(_i64p), _ptr(ci) if ci.size else None, int(max_successors),
-                                    W_act.data_ptr(), act_ids.data_ptr(), int(W_act.shape[0]),
+                                    W_act.data_ptr(), act_ids.data_ptr(), int(V_act), int(layout),
                                     workspace.data_ptr(), int(workspace.numel()),
                                     torch.cuda.current_stream().cuda_stream, _ptr(slots), _ptr(ids), ctypes.byref(n)),
            "evospec_path_a_event")

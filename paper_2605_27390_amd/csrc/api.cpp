@@ -37,6 +37,8 @@ int device_num_cu(int* out) {
     return EVOSPEC_OK;
 }
 
+bool bad_layout(int layout) { return layout != EVOSPEC_ROW_MAJOR && layout != EVOSPEC_PACKED; }
+
 int check_head_args(const void* h, int M, int d, const void* W, int V_act, int k) {
     if (M < 0 || d <= 0 || (d % 8) != 0 || V_act <= 0) return EVOSPEC_BAD_SHAPE;
     if (k < 1 || k > EVOSPEC_K_MAX || k > V_act) return EVOSPEC_BAD_K;
@@ -78,11 +80,20 @@ const char* evospec_status_string(int status) {
         case EVOSPEC_BAD_SEGMENTS: return "row_off must start at 0, be non-decreasing and end at M";
         case EVOSPEC_INVALID_IDS: return "ids out of range or not unique";
         case EVOSPEC_HIP_ERROR: return "HIP error (see evospec_last_hip_error)";
+        case EVOSPEC_BAD_LAYOUT: return "layout must be EVOSPEC_ROW_MAJOR or EVOSPEC_PACKED";
         default: return "unknown status";
     }
 }
 
 const char* evospec_last_hip_error(void) { return g_hip_error; }
+
+int evospec_matrix_bytes(int rows, int d, int layout, size_t* out_bytes) {
+    if (!out_bytes) return EVOSPEC_NULL_POINTER;
+    if (rows < 0 || d <= 0 || (d % 8) != 0) return EVOSPEC_BAD_SHAPE;
+    if (bad_layout(layout)) return EVOSPEC_BAD_LAYOUT;
+    *out_bytes = matrix_elems((size_t)rows, d, layout == EVOSPEC_PACKED) * 2;
+    return EVOSPEC_OK;
+}
 
 int evospec_workspace_bytes(int M, int V_act, int d, int k, size_t* out_bytes) {
     if (!out_bytes) return EVOSPEC_NULL_POINTER;
@@ -109,21 +120,24 @@ int evospec_workspace_bytes_segmented(int M, int V_core, int V_arc, int S, int d
 }
 
 int evospec_active_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
-                          int n, void* W_act, int32_t* act_ids, int V_act, void* stream) {
+                          int n, void* W_act, int32_t* act_ids, int V_act, int layout, void* stream) {
     if (V <= 0 || d <= 0 || (d % 8) != 0 || V_act <= 0 || n < 0) return EVOSPEC_BAD_SHAPE;
+    if (bad_layout(layout)) return EVOSPEC_BAD_LAYOUT;
     if (!slots && n > V_act) return EVOSPEC_BAD_SHAPE;
     if (n == 0) return EVOSPEC_OK;
     if (!W_lm || !src_ids || !W_act || !act_ids) return EVOSPEC_NULL_POINTER;
     if (!aligned16(W_lm) || !aligned16(W_act)) return EVOSPEC_MISALIGNED;
     hipError_t e = launch_gather(W_lm, V, d, src_ids, slots, n, W_act, act_ids, V_act,
-                                 static_cast<hipStream_t>(stream));
+                                 static_cast<hipStream_t>(stream), layout == EVOSPEC_PACKED);
     return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
 }
 
 int evospec_active_lmhead_partials(const void* h, int M, int d, const void* W_act, const int32_t* ids,
-                                   int V_act, int k, void* workspace, size_t workspace_bytes, void* stream) {
+                                   int V_act, int layout, int k, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
     int rc = check_head_args(h, M, d, W_act, V_act, k);
     if (rc) return rc;
+    if (bad_layout(layout)) return EVOSPEC_BAD_LAYOUT;
     if (M == 0) return EVOSPEC_OK;
     if (M > kMTile) return EVOSPEC_BAD_SHAPE;          // the split halves handle one 64-row pass
     if (!workspace) return EVOSPEC_NULL_POINTER;
@@ -135,7 +149,7 @@ int evospec_active_lmhead_partials(const void* h, int M, int d, const void* W_ac
     const Plan p = make_plan(M, V_act, k, num_cu);
     char* ws = static_cast<char*>(workspace);
     hipError_t e = launch_partials(p, h, M, d, W_act, ids, V_act, k, ws + p.keys_off, ws + p.stats_off,
-                                   static_cast<hipStream_t>(stream));
+                                   static_cast<hipStream_t>(stream), layout == EVOSPEC_PACKED);
     return e == hipSuccess ? EVOSPEC_OK : hip_fail(e);
 }
 
@@ -164,10 +178,12 @@ int evospec_active_lmhead_merge(int M, int V_act, int d, int k, float* out_vals,
 namespace {
 // The head, with an optional update that rides on its last merge launch.
 int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids,
-              int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
+              int V_act, int layout, int k, float* out_vals, int32_t* out_ids, float* out_logz,
               void* workspace, size_t workspace_bytes, void* stream, const GatherArgs* update) {
     int rc = check_head_args(h, M, d, W_act, V_act, k);
     if (rc) return rc;
+    if (bad_layout(layout)) return EVOSPEC_BAD_LAYOUT;
+    const bool packed = layout == EVOSPEC_PACKED;
     if (M == 0) return EVOSPEC_OK;
     if (!out_vals || !out_ids || !out_logz || !workspace) return EVOSPEC_NULL_POINTER;
     if (!aligned16(workspace)) return EVOSPEC_MISALIGNED;
@@ -182,7 +198,7 @@ int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids
     const uint16_t* hp = static_cast<const uint16_t*>(h);
     if (use_gemm(M, d)) {                               // bound by the contraction: all rows at once
         const GemmPlan gp = make_gemm_plan(M, V_act, k);
-        hipError_t e = launch_gemm_partials(h, M, d, W_act, ids, V_act, k, ws + gp.keys_off, ws + gp.stats_off, st);
+        hipError_t e = launch_gemm_partials(h, M, d, W_act, ids, V_act, k, ws + gp.keys_off, ws + gp.stats_off, st, packed);
         if (e != hipSuccess) return hip_fail(e);
         MergeSet a{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len, true};
         MergeSet none{};
@@ -193,7 +209,7 @@ int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids
         const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
         const Plan p = make_plan(rows, V_act, k, num_cu);
         hipError_t e = launch_partials(p, hp + (size_t)m0 * d, rows, d, W_act, ids, V_act, k,
-                                       ws + p.keys_off, ws + p.stats_off, st);
+                                       ws + p.keys_off, ws + p.stats_off, st, packed);
         if (e != hipSuccess) return hip_fail(e);
         MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0, kMTile};
         MergeSet none{};
@@ -207,40 +223,43 @@ int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids
 extern "C" {
 
 int evospec_active_lmhead_topk(const void* h, int M, int d, const void* W_act, const int32_t* ids,
-                               int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
+                               int V_act, int layout, int k, float* out_vals, int32_t* out_ids, float* out_logz,
                                void* workspace, size_t workspace_bytes, void* stream) {
-    return head_impl(h, M, d, W_act, ids, V_act, k, out_vals, out_ids, out_logz, workspace, workspace_bytes,
+    return head_impl(h, M, d, W_act, ids, V_act, layout, k, out_vals, out_ids, out_logz, workspace, workspace_bytes,
                      stream, nullptr);
 }
 
 int evospec_active_lmhead_topk_then_update(const void* h, int M, int d, void* W_act, int32_t* act_ids,
-                                           int V_act, int k, float* out_vals, int32_t* out_ids, float* out_logz,
-                                           void* workspace, size_t workspace_bytes,
+                                           int V_act, int layout, int k, float* out_vals, int32_t* out_ids,
+                                           float* out_logz, void* workspace, size_t workspace_bytes,
                                            const void* W_lm, int V, const int32_t* src_ids, const int32_t* slots,
                                            int n, void* stream) {
     if (V <= 0 || n < 0) return EVOSPEC_BAD_SHAPE;
+    if (bad_layout(layout)) return EVOSPEC_BAD_LAYOUT;
     if (!slots && n > V_act) return EVOSPEC_BAD_SHAPE;
     if (n > 0 && (!W_lm || !src_ids || !act_ids)) return EVOSPEC_NULL_POINTER;
     if (n > 0 && !aligned16(W_lm)) return EVOSPEC_MISALIGNED;
     if (M == 0 || n == 0) {                       // nothing to ride on, or nothing to carry
-        int rc = head_impl(h, M, d, W_act, act_ids, V_act, k, out_vals, out_ids, out_logz, workspace,
+        int rc = head_impl(h, M, d, W_act, act_ids, V_act, layout, k, out_vals, out_ids, out_logz, workspace,
                            workspace_bytes, stream, nullptr);
         if (rc || n == 0) return rc;
-        return evospec_active_gather(W_lm, V, d, src_ids, slots, n, W_act, act_ids, V_act, stream);
+        return evospec_active_gather(W_lm, V, d, src_ids, slots, n, W_act, act_ids, V_act, layout, stream);
     }
-    const GatherArgs upd{W_lm, V, d / 8, src_ids, slots, n, W_act, act_ids, V_act};
-    return head_impl(h, M, d, W_act, act_ids, V_act, k, out_vals, out_ids, out_logz, workspace, workspace_bytes,
+    const GatherArgs upd{W_lm, V, d / 8, src_ids, slots, n, W_act, act_ids, V_act, layout == EVOSPEC_PACKED ? 1 : 0};
+    return head_impl(h, M, d, W_act, act_ids, V_act, layout, k, out_vals, out_ids, out_logz, workspace, workspace_bytes,
                      stream, &upd);
 }
 
 int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void* W_core,
                                          const int32_t* ids_core, int V_core, const void* W_arc,
-                                         const int32_t* ids_arc, int V_arc, const int32_t* row_off, int S,
-                                         int k, float* out_vals, int32_t* out_ids, float* out_logz,
+                                         const int32_t* ids_arc, int V_arc, int layout, const int32_t* row_off,
+                                         int S, int k, float* out_vals, int32_t* out_ids, float* out_logz,
                                          void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || d <= 0 || (d % 8) != 0 || V_core < 0 || V_arc < 0 || V_core + V_arc <= 0 || S <= 0)
         return EVOSPEC_BAD_SHAPE;
     if (k < 1 || k > EVOSPEC_K_MAX || k > V_core + V_arc) return EVOSPEC_BAD_K;
+    if (bad_layout(layout)) return EVOSPEC_BAD_LAYOUT;
+    const bool packed = layout == EVOSPEC_PACKED;
     if (!row_off) return EVOSPEC_NULL_POINTER;
     if (row_off[0] != 0 || row_off[S] != M) return EVOSPEC_BAD_SEGMENTS;
     for (int s = 0; s < S; ++s)
@@ -271,7 +290,7 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
     if (gemm_core) {
         const GemmPlan gp = make_gemm_plan(M, V_core, k);
         hipError_t e = launch_gemm_partials(h, M, d, W_core, ids_core, V_core, k, ws + gp.keys_off,
-                                            ws + gp.stats_off, st);
+                                            ws + gp.stats_off, st, packed);
         if (e != hipSuccess) return hip_fail(e);
         core = MergeSet{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len, true};
     } else if (V_core > 0) {
@@ -280,7 +299,7 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
             const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
             char* w = ws + (size_t)pss * core_stride;
             hipError_t e = launch_partials(pc, hp + (size_t)m0 * d, rows, d, W_core, ids_core, V_core, k,
-                                           w + pc.keys_off, w + pc.stats_off, st);
+                                           w + pc.keys_off, w + pc.stats_off, st, packed);
             if (e != hipSuccess) return hip_fail(e);
         }
         core = MergeSet{ws + pc.keys_off, ws + pc.stats_off, pc.n_slabs, 0, kMTile};
@@ -301,6 +320,7 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
             BatchLayout bl;
             bl.seq_rows = V_arc;
             bl.chunk_bytes = arc_stride;
+            bl.packed = packed;
             hipError_t e = launch_partials_batch(pa, h, cb, bl, d, W_arc, ids_arc, V_arc, k,
                                                  ws_arc + pa.keys_off, ws_arc + pa.stats_off, st);
             if (e != hipSuccess) return hip_fail(e);

@@ -290,7 +290,7 @@ int evospec_path_a_workspace_bytes(int V, int d, int n_mips, int max_insert, siz
 int evospec_path_a_event(evospec_arc* arc, const void* h_target, int d, const void* W_lm, int V,
                          const int32_t* target_top, int n_target, int n_mips,
                          const int64_t* row_ptr, const int32_t* col_idx, int max_successors,
-                         void* W_act, int32_t* act_ids, int V_act,
+                         void* W_act, int32_t* act_ids, int V_act, int layout,
                          void* workspace, size_t workspace_bytes, void* stream,
                          int32_t* out_slots, int32_t* out_ids, int* n_out) {
     if (!arc || !n_out || !workspace) return EVOSPEC_NULL_POINTER;
@@ -310,7 +310,7 @@ int evospec_path_a_event(evospec_arc* arc, const void* h_target, int d, const vo
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     // 1. exact search over the full vocabulary (identity ids), ids to the host
-    rc = evospec_active_lmhead_topk(h_target, 1, d, W_lm, nullptr, V, n_mips, top_vals, top_ids, top_logz,
+    rc = evospec_active_lmhead_topk(h_target, 1, d, W_lm, nullptr, V, EVOSPEC_ROW_MAJOR, n_mips, top_vals, top_ids, top_logz,
                                     workspace, head, stream);
     if (rc) return rc;
     int32_t mips[EVOSPEC_K_MAX];
@@ -339,7 +339,7 @@ int evospec_path_a_event(evospec_arc* arc, const void* h_target, int d, const vo
     if (hipMemcpyAsync(upd, pairs.data(), (size_t)n_ins * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
         hipMemcpyAsync(upd + cap, pairs.data() + cap, (size_t)n_ins * 4, hipMemcpyHostToDevice, st) != hipSuccess)
         return EVOSPEC_HIP_ERROR;
-    return evospec_active_gather(W_lm, V, d, upd + cap, upd, n_ins, W_act, act_ids, V_act, stream);
+    return evospec_active_gather(W_lm, V, d, upd + cap, upd, n_ins, W_act, act_ids, V_act, layout, stream);
 }
 
 }  // extern "C"

@@ -115,6 +115,9 @@ __device__ __forceinline__ void quad_all(uint32_t x, uint32_t (&q)[4]) {
 
 }  // namespace
 
+// PACKED: W is in operand-tile layout (plan.hpp): a wave-level load then takes one whole 1 KB
+// operand block (16 rows x 32 hidden elements), which lands in LDS in the order the lanes read it.
+template <bool PACKED>
 __global__ void __launch_bounds__(256, 1)
 lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
                    const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, int V_act, int k, int list_len,
@@ -147,7 +150,14 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
         const int r = (kPLoads * w + i) * 8 + ((lane >> 2) & 7);
         const int piece = (lane & 3) ^ swz(r);
         const int half = lane >> 5;
-        asrc[i] = W + (size_t)min(v0 + r, V_act - 1) * d + half * kGK + piece * 8;   // rows past the end repeat
+        if constexpr (PACKED) {
+            // block B = 8 w + i of the pair-stage: k-step parity B & 1 of the 16-row tile B >> 1
+            const int B = kPLoads * w + i;
+            const int tile = min((v0 >> 4) + (B >> 1), (V_act - 1) >> 4);            // tiles past the end repeat the last
+            asrc[i] = W + (size_t)tile * kPackRows * packed_d(d) + (B & 1) * (16 * kGK) + lane * 8;
+        } else {
+            asrc[i] = W + (size_t)min(v0 + r, V_act - 1) * d + half * kGK + piece * 8;   // rows past the end repeat
+        }
         bsrc[i] = h + (size_t)min(m0 + r, M - 1) * d + half * kGK + piece * 8;       // the last one, masked later
     }
     const int nchunks = d / kGK;                                   // even: d is a multiple of 64 here
@@ -157,7 +167,8 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
     auto issue_one = [&](int p, int j) {
         const size_t koff = (size_t)min(p, npairs - 1) * (2 * kGK);
         unsigned char* dst = smem + (p & 1) * kPairBytes + (j & 1) * (2 * kGOperandBytes) + (kPLoads * w + (j >> 1)) * 1024;
-        const uint16_t* src = ((j & 1) ? bsrc[j >> 1] : asrc[j >> 1]) + koff;
+        // (a k-step of a packed tile is 16 rows x 32 elements long)
+        const uint16_t* src = (j & 1) ? bsrc[j >> 1] + koff : asrc[j >> 1] + (PACKED ? koff * 16 : koff);
         __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
     };
 
@@ -170,12 +181,13 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
     // operand reads: lane (n16, g) takes piece g of row n16 of each 16-row block of its quadrant;
     // row R of an operand sits in block R / 8 at row R % 8
     auto row_off = [&](int R) { return (R >> 3) * 1024 + (R & 7) * 64; };
-    const int a_rd = row_off(wv * 128 + n16) + ((g ^ swz(n16)) * 16);
+    const int a_rd = PACKED ? wv * 128 * 128 + lane * 16 : row_off(wv * 128 + n16) + ((g ^ swz(n16)) * 16);
+    constexpr int kAParity = PACKED ? 1024 : 512;                  // second chunk of a pair, W side
     const int b_rd = 2 * kGOperandBytes + row_off(wm * 128 + n16) + ((g ^ swz(n16)) * 16);
     bf16x8 opa[2][8], opb[2][8];
     auto stage_of = [&](int c) { return ((c >> 1) & 1) * kPairBytes + (c & 1) * 512; };
     auto read_a = [&](auto SET, int c, int i) {
-        opa[decltype(SET)::value][i] = *reinterpret_cast<const bf16x8*>(smem + stage_of(c) + a_rd + i * 2048);
+        opa[decltype(SET)::value][i] = *reinterpret_cast<const bf16x8*>(smem + ((c >> 1) & 1) * kPairBytes + (c & 1) * kAParity + a_rd + i * 2048);
     };
     auto read_b = [&](auto SET, int c, int i) {
         opb[decltype(SET)::value][i] = *reinterpret_cast<const bf16x8*>(smem + stage_of(c) + b_rd + i * 2048);
@@ -493,20 +505,22 @@ lmhead_gemm_kernel(const uint16_t* __restrict__ h, int M, int d,
 }
 
 hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, const int32_t* ids, int V_act,
-                                int k, void* keys, void* stats, hipStream_t stream) {
+                                int k, void* keys, void* stats, hipStream_t stream, bool packed) {
     const int v_tiles = (V_act + kGemmTile - 1) / kGemmTile;
     const int m_tiles = (M + kGemmTile - 1) / kGemmTile;
     if (d % (2 * kGK) != 0 || d < 2 * kGK) return hipErrorInvalidValue;      // callers route such d elsewhere
-    auto kern = lmhead_gemm_kernel;
+    auto kern = packed ? lmhead_gemm_kernel<true> : lmhead_gemm_kernel<false>;
     constexpr int kMaxDevices = 64;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevices || !attr_set[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGLdsTotal);
-        if (e != hipSuccess) return e;
+        for (auto kf : {lmhead_gemm_kernel<true>, lmhead_gemm_kernel<false>}) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kf),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGLdsTotal);
+            if (e != hipSuccess) return e;
+        }
         if (dev >= 0 && dev < kMaxDevices) attr_set[dev] = true;
     }
     hipLaunchKernelGGL(kern, dim3(v_tiles * m_tiles), dim3(256), kGLdsTotal, stream,

@@ -18,25 +18,46 @@ namespace evospec {
 
 // ---------------------------------------------------------------------------------------
 // Row insertion  W_act[slot] <- W_lm[id], act_ids[slot] <- id  (bit copy, 16 B per lane).
-// One workgroup per row.
+// One workgroup per row.  Into a packed W_act the row's pieces go to their places in the operand
+// tiles (16-byte stores 256 bytes apart) and the pieces between d and the padded row length are
+// zeroed.
 __device__ __forceinline__ void gather_one_row(const GatherArgs& g, int i) {
     const int32_t id = g.src_ids[i];
     const int32_t s = g.slots ? g.slots[i] : i;
     if (id < 0 || id >= g.V || s < 0 || s >= g.V_act) return;      // uniform per workgroup
     const uint4* src = static_cast<const uint4*>(g.W_lm) + (size_t)id * g.row_vec;
-    uint4* dst = static_cast<uint4*>(g.W_act) + (size_t)s * g.row_vec;
     const int nt = blockDim.x;
-    for (int c0 = 0; c0 < g.row_vec; c0 += 4 * nt) {
-        uint4 v[4];
+    if (g.packed) {
+        const int dp_vec = packed_d(g.row_vec * 8) / 8;
+        uint4* dst = static_cast<uint4*>(g.W_act) + (size_t)(s >> 4) * (kPackRows * (size_t)dp_vec) + (s & 15);
+        for (int c0 = 0; c0 < dp_vec; c0 += 4 * nt) {
+            uint4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = c0 + u * nt + threadIdx.x;
-            if (c < g.row_vec) v[u] = src[c];
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * nt + threadIdx.x;
+                v[u] = make_uint4(0u, 0u, 0u, 0u);
+                if (c < g.row_vec) v[u] = src[c];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * nt + threadIdx.x;
+                if (c < dp_vec) dst[(c >> 2) * 64 + (c & 3) * 16] = v[u];
+            }
         }
+    } else {
+        uint4* dst = static_cast<uint4*>(g.W_act) + (size_t)s * g.row_vec;
+        for (int c0 = 0; c0 < g.row_vec; c0 += 4 * nt) {
+            uint4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = c0 + u * nt + threadIdx.x;
-            if (c < g.row_vec) dst[c] = v[u];
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * nt + threadIdx.x;
+                if (c < g.row_vec) v[u] = src[c];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * nt + threadIdx.x;
+                if (c < g.row_vec) dst[c] = v[u];
+            }
         }
     }
     if (threadIdx.x == 0) g.act_ids[s] = id;
@@ -46,6 +67,39 @@ __device__ __forceinline__ void gather_one_row(const GatherArgs& g, int i) {
 __global__ void __launch_bounds__(256)
 gather_rows_kernel(GatherArgs g) {
     for (int i = blockIdx.x; i < g.n; i += gridDim.x) gather_one_row(g, i);
+}
+
+// Rebuild of a packed W_act (slot i = i): one workgroup per tile of 16 slots, so that every 1 KB
+// operand block is written whole by one wave-level store.  Lane 16 g + n of a wavefront reads piece
+// 4 s + g of the row that goes to slot 16 t + n, for the k-steps s = wave, wave + 4, ...
+__global__ void __launch_bounds__(256)
+gather_tiles_kernel(GatherArgs g) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int n16 = lane & 15, gq = lane >> 4;
+    const int dp_vec = packed_d(g.row_vec * 8) / 8;
+    const int nsteps = dp_vec / 4;
+    for (int t = blockIdx.x; t * kPackRows < g.n; t += gridDim.x) {
+        const int i = t * kPackRows + n16;
+        const int32_t id = i < g.n ? g.src_ids[i] : -1;
+        const bool ok = id >= 0 && id < g.V && i < g.V_act;
+        const uint4* src = static_cast<const uint4*>(g.W_lm) + (size_t)(ok ? id : 0) * g.row_vec;
+        uint4* dst = static_cast<uint4*>(g.W_act) + (size_t)t * (kPackRows * (size_t)dp_vec) + lane;
+        for (int s0 = w; s0 < nsteps; s0 += 16) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = 4 * (s0 + 4 * u) + gq;
+                v[u] = make_uint4(0u, 0u, 0u, 0u);
+                if (ok && c < g.row_vec) v[u] = src[c];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + 4 * u;
+                if (ok && s < nsteps) dst[(size_t)s * 64] = v[u];
+            }
+        }
+        if (ok && w == 0 && gq == 0) g.act_ids[i] = id;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -79,7 +133,7 @@ validate_ids_kernel(const int32_t* __restrict__ ids, int n, int V, int* flag) {
 //   part_stats[slab][m] = (max_i z, sum_i exp(z - max))         over the slab's rows
 //   part_keys[slab][m][0..k) = the slab's k best keys, descending (0 = none)
 // Logits never leave the CU.
-template <int NW, int RGW, int RC, int MB, bool FULLK>
+template <int NW, int RGW, int RC, int MB, bool FULLK, bool PACKED>
 __global__ void __launch_bounds__(NW * 64)
 lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int seq_rows,
                        size_t chunk_keys, size_t chunk_stats, int d,
@@ -92,7 +146,10 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
     const int rows = cb.rows[ci];
     const size_t seq_row0 = (size_t)cb.seq[ci] * seq_rows;
     const uint16_t* __restrict__ h = h_all + (size_t)cb.m0[ci] * d;
-    const uint16_t* __restrict__ W = W_all + seq_row0 * d;
+    // (a packed matrix pads every sequence's rows to whole tiles and its rows to whole chunks)
+    const int dp = packed_d(d);
+    const uint16_t* __restrict__ W = PACKED ? W_all + (size_t)cb.seq[ci] * packed_rows(seq_rows) * dp
+                                            : W_all + seq_row0 * d;
     const int32_t* __restrict__ ids = ids_all ? ids_all + seq_row0 : nullptr;
     u64* __restrict__ part_keys = keys_all + (size_t)ci * chunk_keys;
     float2* __restrict__ part_stats = stats_all + (size_t)ci * chunk_stats;
@@ -133,9 +190,15 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
     const uint16_t* wp[RGW];
 #pragma unroll
     for (int rg = 0; rg < RGW; ++rg) {
-        int r = row0 + (w * RGW + rg) * 16 + n16;
-        r = min(r, V_act - 1);                         // tail slab: duplicate a valid row, masked later
-        wp[rg] = W + (size_t)r * d + g * 8;
+        if constexpr (PACKED) {
+            // the wavefront's tile: 1 KB operand blocks in k-step order, lane l at byte 16 l
+            const int tile = min((row0 >> 4) + w * RGW + rg, (V_act - 1) >> 4);   // tail slab: a valid tile, masked later
+            wp[rg] = W + (size_t)tile * kPackRows * dp + lane * 8;
+        } else {
+            int r = row0 + (w * RGW + rg) * 16 + n16;
+            r = min(r, V_act - 1);                         // tail slab: duplicate a valid row, masked later
+            wp[rg] = W + (size_t)r * d + g * 8;
+        }
     }
 
     f32x4 acc[RGW][MB];
@@ -191,7 +254,9 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
         const int koff = c * KC + s * 32;
 #pragma unroll
         for (int rg = 0; rg < RGW; ++rg) {
-            if constexpr (FULLK) {
+            if constexpr (PACKED) {
+                wr[rg][slot] = wsrc[rg][(koff / 32) * 64];       // rows are padded to whole chunks
+            } else if constexpr (FULLK) {
                 wr[rg][slot] = wsrc[rg][koff / 8];
             } else {
                 const bool in = koff + g * 8 < d;
@@ -600,11 +665,11 @@ namespace evospec {
 namespace {
 constexpr int kMaxDevices = 64;
 
-template <int NW, int RGW, int RC, int MB, bool FULLK>
+template <int NW, int RGW, int RC, int MB, bool FULLK, bool PACKED>
 hipError_t launch_partials_k(const Plan& p, const void* h, const ChunkBatch& cb, const BatchLayout& bl, int d,
                              const void* W, const int32_t* ids, int V_act, int k, void* keys, void* stats,
                              hipStream_t stream) {
-    auto kern = lmhead_partials_kernel<NW, RGW, RC, MB, FULLK>;
+    auto kern = lmhead_partials_kernel<NW, RGW, RC, MB, FULLK, PACKED>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -627,12 +692,18 @@ hipError_t launch_partials_shape(const Plan& p, const void* h, const ChunkBatch&
                                  const void* W, const int32_t* ids, int V_act, int k, void* keys, void* stats,
                                  hipStream_t stream) {
     const bool full = d % kKC == 0;
+#define EVOSPEC_ARGS p, h, cb, bl, d, W, ids, V_act, k, keys, stats, stream
 #define EVOSPEC_MB(MB_)                                                                              \
-    if (p.mb == MB_)                                                                                 \
-        return full ? launch_partials_k<NW, RGW, RC, MB_, true>(p, h, cb, bl, d, W, ids, V_act, k, keys, stats, stream)   \
-                    : launch_partials_k<NW, RGW, RC, MB_, false>(p, h, cb, bl, d, W, ids, V_act, k, keys, stats, stream);
+    if (p.mb == MB_) {                                                                               \
+        if (bl.packed)                                                                               \
+            return full ? launch_partials_k<NW, RGW, RC, MB_, true, true>(EVOSPEC_ARGS)              \
+                        : launch_partials_k<NW, RGW, RC, MB_, false, true>(EVOSPEC_ARGS);            \
+        return full ? launch_partials_k<NW, RGW, RC, MB_, true, false>(EVOSPEC_ARGS)                 \
+                    : launch_partials_k<NW, RGW, RC, MB_, false, false>(EVOSPEC_ARGS);               \
+    }
     EVOSPEC_MB(1) EVOSPEC_MB(2) EVOSPEC_MB(4)
 #undef EVOSPEC_MB
+#undef EVOSPEC_ARGS
     return hipErrorInvalidValue;
 }
 }  // namespace
@@ -651,10 +722,12 @@ hipError_t launch_partials_batch(const Plan& p, const void* h, const ChunkBatch&
 
 hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
                            const int32_t* ids, int V_act, int k, void* keys, void* stats,
-                           hipStream_t stream) {
+                           hipStream_t stream, bool packed) {
     ChunkBatch cb;
     cb.n = 1; cb.m0[0] = 0; cb.rows[0] = rows; cb.seq[0] = 0; cb.a_pass[0] = 0; cb.a_slot[0] = 0;
-    return launch_partials_batch(p, h, cb, BatchLayout{}, d, W, ids, V_act, k, keys, stats, stream);
+    BatchLayout bl;
+    bl.packed = packed;
+    return launch_partials_batch(p, h, cb, bl, d, W, ids, V_act, k, keys, stats, stream);
 }
 
 hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const MergeSet& b, size_t b_chunk_bytes,
@@ -712,9 +785,14 @@ hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_
 }
 
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
-                         int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream) {
+                         int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream, bool packed) {
+    const GatherArgs g{W_lm, V, d / 8, src_ids, slots, n, W_act, act_ids, V_act, packed ? 1 : 0};
+    if (packed && !slots) {                      // rebuild: whole operand tiles per workgroup
+        const int tiles = (n + kPackRows - 1) / kPackRows;
+        hipLaunchKernelGGL(gather_tiles_kernel, dim3(tiles < 8192 ? tiles : 8192), dim3(256), 0, stream, g);
+        return hipGetLastError();
+    }
     const int grid = n < 8192 ? n : 8192;
-    const GatherArgs g{W_lm, V, d / 8, src_ids, slots, n, W_act, act_ids, V_act};
     hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(256), 0, stream, g);
     return hipGetLastError();
 }

@@ -26,6 +26,7 @@ struct MergeSet {
 struct BatchLayout {
     int seq_rows = 0;
     size_t chunk_bytes = 0;
+    bool packed = false;            // the matrix is in operand-tile layout (plan.hpp), one padded matrix per sequence
 };
 
 hipError_t launch_partials_batch(const Plan& p, const void* h, const ChunkBatch& cb, const BatchLayout& bl,
@@ -40,16 +41,17 @@ hipError_t launch_merge_batch(const MergeSet& a, size_t a_pass_bytes, const Merg
                               float* out_logz, hipStream_t stream, const GatherArgs* update = nullptr);
 hipError_t launch_partials(const Plan& p, const void* h, int rows, int d, const void* W,
                            const int32_t* ids, int V_act, int k, void* keys, void* stats,
-                           hipStream_t stream);
+                           hipStream_t stream, bool packed = false);
 // Large-M path: partials of all M draft rows, row-major: keys u64 [M][ceil(V_act/128)][gemm_list_len(k)]
 // in any order, stats float2 [M][ceil(V_act/128)].
 hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, const int32_t* ids, int V_act,
-                                int k, void* keys, void* stats, hipStream_t stream);
+                                int k, void* keys, void* stats, hipStream_t stream, bool packed = false);
 hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_vals, int32_t* out_ids,
                         float* out_logz, int out_row0, int nrows, hipStream_t stream,
                         const GatherArgs* update = nullptr);
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
-                         int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream);
+                         int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream,
+                         bool packed = false);
 // Retained-support KL gate (K <= 256, d * 2 bytes <= 48 KB of LDS); workspace of kl_gate_workspace_bytes.
 size_t kl_gate_workspace_bytes(int E, int V);
 hipError_t launch_kl_gate(const float* z_target, int E, int V, const void* h_draft, int d, const void* W_lm,

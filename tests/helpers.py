@@ -66,3 +66,39 @@ def check_head(gv, gi_, gl, z, ids, k, where=""):
         else:
             exempt += 1
     return dict(max_abs_err=max_err, max_rel_logz=float(rel_lz.max()), exempt_rows=exempt)
+
+
+NAN_BITS = 0x7FC1        # a bf16 NaN: what never-written rows and pad pieces of a packed matrix must not leak
+
+
+def unpack_bits(bits, rows, d, batch=None):
+    """Row-major uint16 [rows, d] (or [batch, rows, d]) from the bits of a packed buffer, and the
+    padded matrix itself: piece (r, c) of the packed layout sits at piece index
+    (r // 16) * (2 * dp) + (c // 4) * 64 + (c % 4) * 16 + r % 16, dp = d rounded up to 256."""
+    dp = (d + 255) // 256 * 256
+    rp = (rows + 15) // 16 * 16
+    n = rp * dp
+    B = 1 if batch is None else batch
+    a = np.asarray(bits[:B * n]).reshape(B, rp // 16, dp // 32, 4, 16, 8)      # [tile][k-step][g][n16][8]
+    full = a.transpose(0, 1, 4, 2, 3, 5).reshape(B, rp, dp)                     # [tile][n16][k-step][g][8]
+    out = full[:, :rows, :d]
+    return (out[0] if batch is None else out), full
+
+
+def new_matrix(ev, rows, d, layout, batch=None):
+    """An uninitialised compact matrix on the GPU: a PackedMatrix pre-filled with NaNs, or a
+    row-major tensor."""
+    import torch
+    if layout == "packed":
+        P = ev.PackedMatrix(rows, d, batch=batch)
+        P.data.view(torch.int16).fill_(NAN_BITS)
+        return P
+    shape = (rows, d) if batch is None else (batch, rows, d)
+    return torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+
+
+def matrix_bits(Wm, batch=None):
+    """Row-major bits (host) of a compact matrix in either layout."""
+    if hasattr(Wm, "rows"):
+        return unpack_bits(bf16_dev_to_bits(Wm.data), Wm.rows, Wm.d, batch=batch)[0]
+    return bf16_dev_to_bits(Wm)

@@ -32,11 +32,11 @@ def test_library_exports_every_declared_symbol(ev):
     assert len(syms) >= 11
     for s in syms:
         assert hasattr(ev.lib, s), f"{s} declared in include/ but not exported"
-    assert ev.version() == 100
+    assert ev.version() == 200
 
 
 def test_status_strings(ev):
-    for code in range(9):
+    for code in range(10):
         assert ev.status_string(code) and ev.status_string(code) != "unknown status"
     assert ev.status_string(99) == "unknown status"
 
@@ -66,6 +66,21 @@ def test_workspace_bytes(ev):
     assert L.evospec_workspace_bytes(1, 1000, 64, 65, ctypes.byref(out)) == 3    # k > K_MAX
 
 
+def test_matrix_bytes(ev):
+    # row-major: rows x d; packed: rows to a multiple of 16, d to a multiple of 256
+    assert ev.matrix_bytes(36864, 4096, ev.ROW_MAJOR) == 36864 * 4096 * 2
+    assert ev.matrix_bytes(36864, 4096, ev.PACKED) == 36864 * 4096 * 2
+    assert ev.matrix_bytes(33, 72, ev.ROW_MAJOR) == 33 * 72 * 2
+    assert ev.matrix_bytes(33, 72, ev.PACKED) == 48 * 256 * 2
+    assert ev.matrix_bytes(0, 64, ev.PACKED) == 0
+    out = ctypes.c_size_t(0)
+    L = ev.lib
+    assert L.evospec_matrix_bytes(10, 64, 0, None) == 1
+    assert L.evospec_matrix_bytes(10, 60, 0, ctypes.byref(out)) == 2
+    assert L.evospec_matrix_bytes(-1, 64, 0, ctypes.byref(out)) == 2
+    assert L.evospec_matrix_bytes(10, 64, 2, ctypes.byref(out)) == 9
+
+
 def test_head_argument_errors_need_no_gpu(ev):
     L = ev.lib
     buf = ctypes.create_string_buffer(4096 + 64)
@@ -75,24 +90,27 @@ def test_head_argument_errors_need_no_gpu(ev):
     f = L.evospec_active_lmhead_topk
     big = 1 << 30
     # every call below fails validation on the host: nothing is ever launched on these host addresses
-    assert f(None, 4, 64, al, None, 100, 5, al, al, al, al, big, None) == 1
-    assert f(al, 4, 64, None, None, 100, 5, al, al, al, al, big, None) == 1
-    assert f(al, 4, 64, al, None, 100, 5, None, al, al, al, big, None) == 1
-    assert f(al, 4, 64, al, None, 100, 5, al, al, al, None, big, None) == 1
-    assert f(al, 4, 60, al, None, 100, 5, al, al, al, al, big, None) == 2
-    assert f(al, -1, 64, al, None, 100, 5, al, al, al, al, big, None) == 2
-    assert f(al, 4, 64, al, None, 0, 5, al, al, al, al, big, None) == 2
-    assert f(al, 4, 64, al, None, 100, 0, al, al, al, al, big, None) == 3
-    assert f(al, 4, 64, al, None, 100, 101, al, al, al, al, big, None) == 3
-    assert f(al, 4, 64, al, None, 100, 65, al, al, al, al, big, None) == 3
-    assert f(mis, 4, 64, al, None, 100, 5, al, al, al, al, big, None) == 4
-    assert f(al, 4, 64, mis, None, 100, 5, al, al, al, al, big, None) == 4
-    assert f(al, 4, 64, al, None, 100, 5, al, al, al, mis, big, None) == 4
-    assert f(al, 4, 64, al, None, 100, 5, al, al, al, al, 16, None) == 5
-    assert f(al, 0, 64, al, None, 100, 5, al, al, al, al, 0, None) == 0             # M == 0: no-op
+    assert f(None, 4, 64, al, None, 100, 0, 5, al, al, al, al, big, None) == 1
+    assert f(al, 4, 64, None, None, 100, 0, 5, al, al, al, al, big, None) == 1
+    assert f(al, 4, 64, al, None, 100, 0, 5, None, al, al, al, big, None) == 1
+    assert f(al, 4, 64, al, None, 100, 0, 5, al, al, al, None, big, None) == 1
+    assert f(al, 4, 60, al, None, 100, 0, 5, al, al, al, al, big, None) == 2
+    assert f(al, -1, 64, al, None, 100, 0, 5, al, al, al, al, big, None) == 2
+    assert f(al, 4, 64, al, None, 0, 0, 5, al, al, al, al, big, None) == 2
+    assert f(al, 4, 64, al, None, 100, 0, 0, al, al, al, al, big, None) == 3
+    assert f(al, 4, 64, al, None, 100, 0, 101, al, al, al, al, big, None) == 3
+    assert f(al, 4, 64, al, None, 100, 0, 65, al, al, al, al, big, None) == 3
+    assert f(mis, 4, 64, al, None, 100, 0, 5, al, al, al, al, big, None) == 4
+    assert f(al, 4, 64, mis, None, 100, 0, 5, al, al, al, al, big, None) == 4
+    assert f(al, 4, 64, al, None, 100, 0, 5, al, al, al, mis, big, None) == 4
+    assert f(al, 4, 64, al, None, 100, 0, 5, al, al, al, al, 16, None) == 5
+    assert f(al, 0, 64, al, None, 100, 0, 5, al, al, al, al, 0, None) == 0             # M == 0: no-op
     g = L.evospec_active_lmhead_partials
-    assert g(al, 65, 64, al, None, 100, 5, al, big, None) == 2                       # one 64-row pass only
-    assert g(al, 4, 64, al, None, 100, 5, al, 16, None) == 5
+    assert g(al, 65, 64, al, None, 100, 0, 5, al, big, None) == 2                       # one 64-row pass only
+    assert g(al, 4, 64, al, None, 100, 0, 5, al, 16, None) == 5
+    assert g(al, 4, 64, al, None, 100, 2, 5, al, big, None) == 9                     # unknown layout
+    assert f(al, 4, 64, al, None, 100, 7, 5, al, al, al, al, big, None) == 9
+    assert f(al, 4, 64, al, None, 100, 1, 5, al, al, al, al, 16, None) == 5            # packed: same checks
 
 
 def test_gather_argument_errors_need_no_gpu(ev):
@@ -101,17 +119,19 @@ def test_gather_argument_errors_need_no_gpu(ev):
     al = ctypes.c_void_p((ctypes.addressof(buf) + 15) // 16 * 16)
     mis = ctypes.c_void_p(al.value + 4)
     f = L.evospec_active_gather
-    assert f(al, 100, 64, al, None, 0, al, al, 10, None) == 0                        # n == 0: no-op
-    assert f(al, 100, 64, al, None, 11, al, al, 10, None) == 2                       # n > V_act without slots
-    assert f(al, 100, 60, al, None, 1, al, al, 10, None) == 2
-    assert f(al, 0, 64, al, None, 1, al, al, 10, None) == 2
-    assert f(al, 100, 64, al, None, -1, al, al, 10, None) == 2
-    assert f(None, 100, 64, al, None, 1, al, al, 10, None) == 1
-    assert f(al, 100, 64, None, None, 1, al, al, 10, None) == 1
-    assert f(al, 100, 64, al, None, 1, None, al, 10, None) == 1
-    assert f(al, 100, 64, al, None, 1, al, None, 10, None) == 1
-    assert f(mis, 100, 64, al, None, 1, al, al, 10, None) == 4
-    assert f(al, 100, 64, al, None, 1, mis, al, 10, None) == 4
+    assert f(al, 100, 64, al, None, 0, al, al, 10, 0, None) == 0                        # n == 0: no-op
+    assert f(al, 100, 64, al, None, 11, al, al, 10, 0, None) == 2                       # n > V_act without slots
+    assert f(al, 100, 60, al, None, 1, al, al, 10, 0, None) == 2
+    assert f(al, 0, 64, al, None, 1, al, al, 10, 0, None) == 2
+    assert f(al, 100, 64, al, None, -1, al, al, 10, 0, None) == 2
+    assert f(None, 100, 64, al, None, 1, al, al, 10, 0, None) == 1
+    assert f(al, 100, 64, None, None, 1, al, al, 10, 0, None) == 1
+    assert f(al, 100, 64, al, None, 1, None, al, 10, 0, None) == 1
+    assert f(al, 100, 64, al, None, 1, al, None, 10, 0, None) == 1
+    assert f(mis, 100, 64, al, None, 1, al, al, 10, 0, None) == 4
+    assert f(al, 100, 64, al, None, 1, mis, al, 10, 0, None) == 4
+    assert f(al, 100, 64, al, None, 1, al, al, 10, 3, None) == 9                     # unknown layout
+    assert f(al, 100, 64, al, None, 11, al, al, 10, 1, None) == 2                    # packed: same checks
 
 
 def test_segment_errors_need_no_gpu(ev):
@@ -124,14 +144,15 @@ def test_segment_errors_need_no_gpu(ev):
     def ro(*v):
         return (ctypes.c_int32 * len(v))(*v)
 
-    args = lambda r, S=2, M=8: (al, M, 64, al, None, 50, al, al, 10, r, S, 5, al, al, al, al, big, None)
+    args = lambda r, S=2, M=8: (al, M, 64, al, None, 50, al, al, 10, 0, r, S, 5, al, al, al, al, big, None)
     assert f(*args(ro(1, 4, 8))) == 6
     assert f(*args(ro(0, 4, 7))) == 6
     assert f(*args(ro(0, 9, 8))) == 6
     assert f(*args(None)) == 1
     assert f(*args(ro(0, 0, 0), M=0)) == 0
-    assert f(al, 8, 64, al, None, 50, al, al, 10, ro(0, 4, 8), 0, 5, al, al, al, al, big, None) == 2
-    assert f(al, 8, 64, al, None, 50, al, al, 10, ro(0, 4, 8), 2, 61, al, al, al, al, big, None) == 3
+    assert f(al, 8, 64, al, None, 50, al, al, 10, 0, ro(0, 4, 8), 0, 5, al, al, al, al, big, None) == 2
+    assert f(al, 8, 64, al, None, 50, al, al, 10, 0, ro(0, 4, 8), 2, 61, al, al, al, al, big, None) == 3
+    assert f(al, 8, 64, al, None, 50, al, al, 10, 5, ro(0, 4, 8), 2, 5, al, al, al, al, big, None) == 9
 
 
 def test_validate_ids_argument_errors(ev):

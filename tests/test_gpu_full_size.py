@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import evospec_inputs as gi
-from helpers import bf16_dev_to_bits, check_head, to_dev_bf16, to_dev_i32
+from helpers import bf16_dev_to_bits, check_head, matrix_bits, new_matrix, to_dev_bf16, to_dev_i32
 
 pytestmark = pytest.mark.gpu
 
@@ -26,8 +26,10 @@ def lm_head():
     return bits, to_dev_bf16(bits)
 
 
-def test_draft60_step_with_update(ev, oracle_mod, lm_head):
-    """Config 2: gather of the 36,864-id active set, a 32-row ARC update, then the head."""
+@pytest.mark.parametrize("layout", ["packed", "row_major"])
+def test_draft60_step_with_update(ev, oracle_mod, lm_head, layout):
+    """Config 2: gather of the 36,864-id active set, a 32-row ARC update, then the head -- the update
+    once as its own call and once behind a head (the call bench.py times)."""
     import torch
     W_bits, W_lm = lm_head
     c = gi.CONFIGS["draft60"]
@@ -35,30 +37,36 @@ def test_draft60_step_with_update(ev, oracle_mod, lm_head):
     ids = gi.active_ids("draft60")
     V_act = ids.shape[0]
     h = gi.gen_h(M, d, gi.SEED_H + 2)
-    W_act = torch.empty((V_act, d), dtype=torch.bfloat16, device="cuda")
+    W_act = new_matrix(ev, V_act, d, layout)
     act_ids = torch.empty((V_act,), dtype=torch.int32, device="cuda")
     ev.active_gather(W_lm, to_dev_i32(ids), None, W_act, act_ids)
     slots, new_ids = gi.arc_update(V, ids, c["n_core"], 32, seed=7000)
     ev.active_gather(W_lm, to_dev_i32(new_ids), to_dev_i32(slots), W_act, act_ids)
     ref_ids = ids.copy()
     ref_ids[slots] = new_ids
-    v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act, act_ids, k)
+    # the head on this state; behind it, in the same call, the next update
+    slots2, new_ids2 = gi.arc_update(V, ref_ids, c["n_core"], 32, seed=7001)
+    v, i, l = ev.active_lmhead_topk_then_update(to_dev_bf16(h), W_act, act_ids, k, W_lm, to_dev_i32(new_ids2),
+                                                to_dev_i32(slots2))
     torch.cuda.synchronize()
-    assert np.array_equal(act_ids.cpu().numpy(), ref_ids)
-    assert ev.validate_ids(act_ids, V)
-    # gathered rows are bit-exact (sampled slots incl. the updated ones; the whole matrix via a checksum)
-    sample = np.concatenate([slots, np.random.default_rng(0).choice(V_act, 256, replace=False)])
-    got = bf16_dev_to_bits(W_act[torch.from_numpy(sample).cuda().long()])
-    assert np.array_equal(got, W_bits[ref_ids[sample]])
-    assert gi.checksum(bf16_dev_to_bits(W_act)) == gi.checksum(W_bits[ref_ids])
     _, _, _, z = oracle_mod.active_lmhead_topk(h, W_bits[ref_ids], ref_ids, k, return_logits=True)
     st = check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, ref_ids, k, "draft60")
     assert st["max_abs_err"] < 1e-4
     assert st["exempt_rows"] < M // 2
+    ref_ids[slots2] = new_ids2
+    assert np.array_equal(act_ids.cpu().numpy(), ref_ids)
+    assert ev.validate_ids(act_ids, V)
+    # gathered rows are bit-exact: every row of the matrix after both updates
+    assert np.array_equal(matrix_bits(W_act), W_bits[ref_ids])
+    v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act, act_ids, k)
+    torch.cuda.synchronize()
+    _, _, _, z = oracle_mod.active_lmhead_topk(h, W_bits[ref_ids], ref_ids, k, return_logits=True)
+    check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, ref_ids, k, "draft60 after the second update")
 
 
+@pytest.mark.parametrize("layout", ["packed", "row_major"])
 @pytest.mark.parametrize("M", [1, 4, 8])
-def test_depth_expansion_rows(ev, oracle_mod, lm_head, M):
+def test_depth_expansion_rows(ev, oracle_mod, lm_head, M, layout):
     """Config 3: 16,384 core + 2,048 ARC ids, M in {1, 4, 8} rows, with a 256-row update."""
     import torch
     W_bits, W_lm = lm_head
@@ -68,7 +76,7 @@ def test_depth_expansion_rows(ev, oracle_mod, lm_head, M):
     V_act = ids.shape[0]
     assert V_act == 18432
     h = gi.gen_h(M, d, gi.SEED_H + 30 + M)
-    W_act = torch.empty((V_act, d), dtype=torch.bfloat16, device="cuda")
+    W_act = new_matrix(ev, V_act, d, layout)
     act_ids = torch.empty((V_act,), dtype=torch.int32, device="cuda")
     ev.active_gather(W_lm, to_dev_i32(ids), None, W_act, act_ids)
     slots, new_ids = gi.arc_update(V, ids, c["n_core"], c["update_rows"], seed=7100 + M)
@@ -77,7 +85,7 @@ def test_depth_expansion_rows(ev, oracle_mod, lm_head, M):
     ref_ids[slots] = new_ids
     v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act, act_ids, k)
     torch.cuda.synchronize()
-    assert gi.checksum(bf16_dev_to_bits(W_act)) == gi.checksum(W_bits[ref_ids])
+    assert gi.checksum(matrix_bits(W_act)) == gi.checksum(W_bits[ref_ids])
     z = oracle_mod.logits(h, W_bits[ref_ids])
     check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, ref_ids, k, f"depth M={M}")
 
@@ -101,7 +109,8 @@ def test_full_vocabulary_head(ev, oracle_mod, lm_head):
     check_head(v2.cpu().numpy(), i2.cpu().numpy(), l2.cpu().numpy(), z[:, ids], ids, k, "pruned-vs-full")
 
 
-def test_batched_serving(ev, oracle_mod, lm_head):
+@pytest.mark.parametrize("layout", ["packed", "row_major"])
+def test_batched_serving(ev, oracle_mod, lm_head, layout):
     """Config 5: 16 sequences x 60 rows, shared 32,768-id core + 2,048 ARC ids per sequence.
     The oracle checks 4 rows of every sequence (first, last and two inside)."""
     import torch
@@ -111,14 +120,17 @@ def test_batched_serving(ev, oracle_mod, lm_head):
     core, arcs = gi.batched_ids(V, c["n_core"], c["n_arc"], S)
     h = gi.gen_h(M, d, gi.SEED_H + 5)
     row_off = np.arange(S + 1, dtype=np.int32) * rps
-    W_core = torch.empty((core.shape[0], d), dtype=torch.bfloat16, device="cuda")
+    W_core = new_matrix(ev, core.shape[0], d, layout)
     ids_core = torch.empty((core.shape[0],), dtype=torch.int32, device="cuda")
     ev.active_gather(W_lm, to_dev_i32(core), None, W_core, ids_core)
-    W_arc = torch.empty((S * arcs.shape[1], d), dtype=torch.bfloat16, device="cuda")
-    ids_arc = torch.empty((S * arcs.shape[1],), dtype=torch.int32, device="cuda")
-    ev.active_gather(W_lm, to_dev_i32(arcs.reshape(-1)), None, W_arc, ids_arc)
-    v, i, l = ev.active_lmhead_topk_segmented(to_dev_bf16(h), W_core, ids_core, W_arc.view(S, arcs.shape[1], d),
-                                              ids_arc.view(S, arcs.shape[1]), row_off, k)
+    Va = arcs.shape[1]
+    W_arc = new_matrix(ev, Va, d, layout, batch=S)
+    ids_arc = torch.empty((S * Va,), dtype=torch.int32, device="cuda")
+    for s in range(S):
+        ev.active_gather(W_lm, to_dev_i32(arcs[s].copy()), None, W_arc.sub(s) if layout == "packed" else W_arc[s],
+                         ids_arc[s * Va:(s + 1) * Va])
+    v, i, l = ev.active_lmhead_topk_segmented(to_dev_bf16(h), W_core, ids_core, W_arc,
+                                              ids_arc.view(S, Va), row_off, k)
     torch.cuda.synchronize()
     v, i, l = v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy()
     assert np.isfinite(v).all() and np.isfinite(l).all() and (i >= 0).all()
@@ -136,6 +148,7 @@ def test_batched_serving(ev, oracle_mod, lm_head):
 @pytest.mark.parametrize("shape", [s for s in gi.SWEEP if s[1] == 4096 and s[0] in
                                    ("default_32000+256", "8k+256", "16k+1024")], ids=lambda s: s[0])
 def test_paper_active_set_sizes(ev, oracle_mod, lm_head, shape):
+    layout = "packed"
     """The active-set sizes of the paper's own experiments (Table 1 and the default setting):
     gather + head against the oracle on every logit."""
     import torch
@@ -144,7 +157,7 @@ def test_paper_active_set_sizes(ev, oracle_mod, lm_head, shape):
     core, arc = gi.core_arc_ids(V, n_core, n_arc, gi.SEED_IDS + 40)
     ids = np.concatenate([core, arc])
     h = gi.gen_h(M, d, gi.SEED_H + 60)
-    W_act = torch.empty((ids.shape[0], d), dtype=torch.bfloat16, device="cuda")
+    W_act = new_matrix(ev, ids.shape[0], d, layout)
     act_ids = torch.empty((ids.shape[0],), dtype=torch.int32, device="cuda")
     ev.active_gather(W_lm, to_dev_i32(ids), None, W_act, act_ids)
     v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), W_act, act_ids, k)
