@@ -486,10 +486,22 @@ __device__ __forceinline__ u64 pair_key(uint32_t zbits, uint32_t id) {
     return id == 0xffffffffu ? 0ull : make_key(__uint_as_float(zbits), (int32_t)id);
 }
 
-__device__ __forceinline__ u64 wave_bcast(u64 x, int src_lane /*uniform*/) {
-    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)x, src_lane);
-    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), src_lane);
-    return ((u64)hi << 32) | lo;
+// Bitonic sort of one key per lane across the wavefront, descending: lane 0 ends with the largest.
+// 21 compare-exchange steps; equal keys (only the empty key 0 repeats) may end in any order.
+__device__ __forceinline__ u64 wave_sort_desc(u64 x, int lane) {
+#pragma unroll
+    for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)x, stride), hi = __shfl_xor((uint32_t)(x >> 32), stride);
+            const u64 y = ((u64)hi << 32) | lo;
+            const bool lower = (lane & stride) == 0;         // this lane is the smaller index of its pair
+            const bool desc = (lane & size) == 0;            // its block is being sorted downwards
+            const bool gt = x > y;
+            x = (gt == (lower == desc)) ? x : y;             // lower lane of a descending block keeps the larger
+        }
+    }
+    return x;
 }
 
 template <int NT>
@@ -570,12 +582,14 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
         sm = (mx == -INFINITY ? 0.f : sm * __expf(mx - nm)) + st.y * __expf(st.x - nm);
         mx = nm;
     }
+    {   // wavefront: the maximum first, then one rescale per lane and a plain sum
+        float wm_ = mx;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const float om = __shfl_xor(mx, o), os = __shfl_xor(sm, o);
-        const float nm = fmaxf(mx, om);
-        sm = (mx == -INFINITY ? 0.f : sm * __expf(mx - nm)) + (om == -INFINITY ? 0.f : os * __expf(om - nm));
-        mx = nm;
+        for (int o = 1; o < 64; o <<= 1) wm_ = fmaxf(wm_, __shfl_xor(wm_, o));
+        sm = mx == -INFINITY ? 0.f : sm * __expf(mx - wm_);
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) sm += __shfl_xor(sm, o);
+        mx = wm_;
     }
     if (lane == 0) { wave_m[w] = mx; wave_s[w] = sm; }
     if (tid == 0) { npend = 0; nqual = 0; }
@@ -598,22 +612,27 @@ lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_key
         const u64* lst = L < total ? list_of(L) : nullptr;
         u64 head = base == 0 ? head_first : (lst ? head_of(L) : 0);
         if (head <= thr) head = 0;                   // cannot improve the running result
-        // (1) rank of this list's head among the wave's 64 heads; the wave's k best go to cand
-        int rank = 0;
-        for (int j = 0; j < 64; ++j) {
-            const u64 o = wave_bcast(head, j);
-            rank += (o > head) || (o == head && j < lane);
+        // (1) the wave's 64 heads, sorted across the lanes; its k best go to cand
+        {
+            const u64 sorted = wave_sort_desc(head, lane);
+            if (lane < k) cand[w * k + lane] = sorted;
         }
-        if (rank < k) cand[w * k + rank] = head;
         if (tid < nrun) cand[NWV * k + tid] = run[cur][tid];
         __syncthreads();
         // (2) bound = k-th largest of (wave bests + running list): k real candidates are >= it
         const int ne = NWV * k + nrun;
-        for (int e = tid; e < ne; e += NT) {
-            const u64 mine = cand[e];
-            int r = 0;
-            for (int j = 0; j < ne; ++j) { const u64 o = cand[j]; r += (o > mine) || (o == mine && j < e); }   // zeros tie: keep the index order
-            if (r == k - 1) tau_s = mine;
+        if (ne <= 64) {                                  // one more sort by the first wavefront
+            if (w == 0) {
+                const u64 c = wave_sort_desc(lane < ne ? cand[lane] : 0ull, lane);
+                if (lane == k - 1) tau_s = c;
+            }
+        } else {
+            for (int e = tid; e < ne; e += NT) {
+                const u64 mine = cand[e];
+                int r = 0;
+                for (int j = 0; j < ne; ++j) { const u64 o = cand[j]; r += (o > mine) || (o == mine && j < e); }   // zeros tie: keep the index order
+                if (r == k - 1) tau_s = mine;
+            }
         }
         __syncthreads();
         // (3) lists (at most k of them) and running entries that reach the bound feed pend; the
