@@ -281,7 +281,8 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
     };
     // One chunk (8 k-steps).  Ring part SLOT (= c % RC) holds this chunk's W operands, loaded RC
     // chunks ago; each slot is refilled with the same k-step of chunk c+RC right after the MFMAs
-    // that consumed it were issued, so RC*KSTEPS*RGW 16-byte loads per lane stay in flight.
+    // that consumed it were issued (packed matrix) or all slots at the end of the chunk (row-major
+    // matrix), so up to RC*KSTEPS*RGW 16-byte loads per lane stay in flight.
     // The h chunk c+1 is fetched into registers meanwhile and published to the other LDS buffer
     // at the end.  In the steady state (chunks c+1 and c+RC exist) there is no branch in here;
     // the last chunks test for them at run time.
@@ -299,11 +300,17 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
             load_b(b1, buf, s + 1);
             __builtin_amdgcn_sched_barrier(0);
             mfma_step(SLOT * KSTEPS + s, b0);
-            if (pw) load_w_step(SLOT * KSTEPS + s, c + RC, s);
+            if (PACKED && pw) load_w_step(SLOT * KSTEPS + s, c + RC, s);
             if (s + 2 < KSTEPS) load_b(b0, buf, s + 2);
             __builtin_amdgcn_sched_barrier(0);
             mfma_step(SLOT * KSTEPS + s + 1, b1);
-            if (pw) load_w_step(SLOT * KSTEPS + s + 1, c + RC, s + 1);
+            if (PACKED && pw) load_w_step(SLOT * KSTEPS + s + 1, c + RC, s + 1);
+        }
+        if (!PACKED && pw) {
+            // row-major rows: the chunk's 8 requests go out together, so that the 512 bytes they
+            // take from each row reach the memory side close in time (measured: 3.5 us of 73)
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) load_w_step(SLOT * KSTEPS + s, c + RC, s);
         }
         if (ph) store_h(buf ^ 1);
         lds_barrier();
