@@ -218,7 +218,14 @@ def main() -> int:
         extra["fullvocab_head_us"] = round(full_us, 2)
         extra["speedup_vs_fullvocab"] = round(full_us / head_us, 3)
         extra["fullvocab_hbm_gbps"] = round(algorithmic_bytes(V, d, M, k) / full_us / 1e3, 1)
-        del ws_full
+        # the unpruned head given the same advantage: all of W_lm copied into the packed layout
+        W_full_p = ev.PackedMatrix(V, d, device=dev)
+        ids_full = torch.empty((V,), dtype=torch.int32, device=dev)
+        ev.active_gather(W_lm, torch.arange(V, dtype=torch.int32, device=dev), None, W_full_p, ids_full)
+        full_p_us = timed(lambda i: ev.active_lmhead_topk(h, W_full_p, None, k, out_v, out_i, out_l, ws_full), 30, warm=5)
+        extra["fullvocab_head_us_packed"] = round(full_p_us, 2)
+        extra["speedup_vs_fullvocab_packed"] = round(full_p_us / head_us, 3)
+        del ws_full, W_full_p, ids_full
         # per-depth tree expansion: 16,384 core + 2,048 ARC ids, M in {1, 4, 8}, and a 256-row update
         cd = gi.CONFIGS["depth"]
         ids_d = gi.active_ids("depth")
