@@ -200,6 +200,22 @@ def main() -> int:
             extra["step_us_separate_calls"] = round(timed(step_separate, n_ev), 2)
             extra["gather32_us"] = round(timed(
                 lambda i: ev.active_gather(W_lm, upd_ids[0], upd_slots[0], W_acts[0], act_ids[0]), n_ev), 2)
+        if upd_slots:
+            # the same step replayed from a HIP graph (one graph = one step on each W_act copy)
+            try:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(graph, stream=side):
+                        for r in range(R):
+                            ev.active_lmhead_topk_then_update(h, W_acts[r], act_ids[r], k, W_lm, upd_ids[0], upd_slots[0],
+                                                              out_v, out_i, out_l, ws)
+                torch.cuda.current_stream().wait_stream(side)
+                extra["step_us_graph_replay"] = round(timed(lambda i: graph.replay(), max(5, n_ev // R), warm=3) / R, 2)
+                del graph
+            except Exception as exc:                      # reported, never fatal for the benchmark line
+                extra["step_us_graph_replay"] = f"failed: {type(exc).__name__}"
         extra["gather_full_us"] = round(timed(
             lambda i: ev.active_gather(W_lm, ids_dev, None, W_acts[i % R], act_ids[i % R]), 20, warm=3), 2)
         # the same head on a row-major copy of W_act (what a caller's own matrix would be)

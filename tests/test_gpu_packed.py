@@ -281,3 +281,50 @@ def test_packed_path_a_event(ev, oracle_mod):
     v, i, l = ev.active_lmhead_topk(to_dev_bf16(h), ev.PackedMatrix(n_act, d, data=P.data), act_ids[:n_act], 10)
     torch.cuda.synchronize()
     check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), oracle_mod.logits(h, W[active]), active, 10, "after events")
+
+
+# ------------------------------------------------------------------ stream capture
+def test_step_is_capturable_in_a_graph(ev, oracle_mod):
+    """The calls allocate nothing and never synchronise, so a decode step (head + update behind it)
+    can be captured in a HIP graph: every replay, with eager work and synchronisations in between,
+    must reproduce the eager result bit for bit."""
+    import torch
+    V, d, n_core, n_arc, k, M = 4000, 256, 700, 100, 10, 60
+    W = gi.gen_W_lm(V, d)
+    ids = np.concatenate(gi.core_arc_ids(V, n_core, n_arc, seed=6))
+    Wd = to_dev_bf16(W)
+    P = new_packed(ev, ids.shape[0], d)
+    act = torch.empty((ids.shape[0],), dtype=torch.int32, device="cuda")
+    ev.active_gather(Wd, to_dev_i32(ids), None, P, act)
+    slots, new_ids = gi.arc_update(V, ids, n_core, 32, seed=77)
+    sd, nd = to_dev_i32(slots), to_dev_i32(new_ids)
+    h = to_dev_bf16(gi.gen_h(M, d, 91))
+    ws = torch.empty(ev.workspace_bytes(M, ids.shape[0], d, k), dtype=torch.uint8, device="cuda")
+    ov = torch.empty((M, k), dtype=torch.float32, device="cuda")
+    oi = torch.empty((M, k), dtype=torch.int32, device="cuda")
+    ol = torch.empty((M,), dtype=torch.float32, device="cuda")
+
+    def step():
+        ev.active_lmhead_topk_then_update(h, P, act, k, Wd, nd, sd, ov, oi, ol, ws)
+
+    step()                                         # eager: applies the update; later steps see the updated set
+    step()
+    torch.cuda.synchronize()
+    want = (ov.clone(), oi.clone(), ol.clone())
+    ref_ids = ids.copy(); ref_ids[slots] = new_ids
+    check_head(ov.cpu().numpy(), oi.cpu().numpy(), ol.cpu().numpy(), oracle_mod.logits(gi.gen_h(M, d, 91), W[ref_ids]),
+               ref_ids, k, "eager step on the updated set")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(4):
+        ov.zero_(); oi.zero_(); ol.zero_()         # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ov, want[0]) and torch.equal(oi, want[1]) and torch.equal(ol, want[2]), f"replay {r}"
+    assert np.array_equal(act.cpu().numpy(), ref_ids)
