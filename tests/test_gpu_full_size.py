@@ -101,6 +101,14 @@ def test_full_vocabulary_head(ev, oracle_mod, lm_head):
     torch.cuda.synchronize()
     z = oracle_mod.logits(h, W_bits)
     check_head(v.cpu().numpy(), i.cpu().numpy(), l.cpu().numpy(), z, None, k, "fullvocab")
+    # the same head on a packed copy of all of W_lm (1,056 slabs of 10 wavefronts): bit-identical
+    W_p = new_matrix(ev, c["V"], c["d"], "packed")
+    scratch_ids = torch.empty((c["V"],), dtype=torch.int32, device="cuda")
+    ev.active_gather(W_lm, torch.arange(c["V"], dtype=torch.int32, device="cuda"), None, W_p, scratch_ids)
+    vp, ip, lp = ev.active_lmhead_topk(to_dev_bf16(h), W_p, None, k)
+    torch.cuda.synchronize()
+    assert torch.equal(vp, v) and torch.equal(ip, i) and torch.equal(lp, l)
+    del W_p, scratch_ids
     # the pruned head's logZ is below the full one, and its top-k is the full top-k filtered to active ids
     ids = gi.active_ids("draft60")
     v2, i2, l2 = ev.active_lmhead_topk(to_dev_bf16(h), to_dev_bf16(W_bits[ids]), to_dev_i32(ids), k)
