@@ -493,24 +493,6 @@ __device__ __forceinline__ u64 pair_key(uint32_t zbits, uint32_t id) {
     return id == 0xffffffffu ? 0ull : make_key(__uint_as_float(zbits), (int32_t)id);
 }
 
-// Bitonic sort of one key per lane across the wavefront, descending: lane 0 ends with the largest.
-// 21 compare-exchange steps; equal keys (only the empty key 0 repeats) may end in any order.
-__device__ __forceinline__ u64 wave_sort_desc(u64 x, int lane) {
-#pragma unroll
-    for (int size = 2; size <= 64; size <<= 1) {
-#pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            const uint32_t lo = __shfl_xor((uint32_t)x, stride), hi = __shfl_xor((uint32_t)(x >> 32), stride);
-            const u64 y = ((u64)hi << 32) | lo;
-            const bool lower = (lane & stride) == 0;         // this lane is the smaller index of its pair
-            const bool desc = (lane & size) == 0;            // its block is being sorted downwards
-            const bool gt = x > y;
-            x = (gt == (lower == desc)) ? x : y;             // lower lane of a descending block keeps the larger
-        }
-    }
-    return x;
-}
-
 template <int NT>
 __global__ void __launch_bounds__(NT)
 lmhead_merge_kernel(PartialSet A, PartialSet B, ChunkBatch cb, size_t a_pass_keys, size_t a_pass_stats,

@@ -6,9 +6,9 @@
 //
 // Four launches:
 //  1. kl_select_slices_kernel, one workgroup of 16 wavefronts per (eighth of the vocabulary, event):
-//     every thread takes the maximum of its share of the slice; the K-th largest of these 1024
-//     maxima is a lower bound of the slice's K-th largest logit, so the logits that reach it (a few
-//     hundred) go to the workspace as 64-bit (logit, id) keys.  If more than 2048 reach it (masses
+//     every thread takes the maximum of its share of the slice; a value that K of these 1024 maxima
+//     reach (from one sort per wavefront) is a lower bound of the slice's K-th largest logit, so the
+//     logits that reach it (a few hundred) go to the workspace as 64-bit (logit, id) keys.  If more than 2048 reach it (masses
 //     of equal logits), radix select on the key instead (11 bits per pass, histogram in LDS, a pass
 //     is skipped as soon as the bin that holds the K-th key is taken whole) leaves exactly K;
 //  2. kl_select_final_kernel, one workgroup per event: the same bound over the slices' candidates,
@@ -109,6 +109,22 @@ __device__ __forceinline__ u64 kth_largest_1024(u64 v, int K, int bits, uint32_t
     }
     return *prefix_s;
 }
+
+// A lower bound of the K-th largest (counting repeats) of the 1024 values v, one per thread, without
+// a selection: every wavefront sorts its 64 values; with q = ceil(K / 16), each of the 16
+// wavefronts holds q values at or above its own q-th largest, so K values reach the smallest of the
+// 16.  (Looser than the exact K-th largest, which costs three radix passes with their barriers.)
+__device__ __forceinline__ u64 kth_bound_1024(u64 v, int K, u64* wave_q /*LDS [16]*/) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int q = (K + 15) >> 4;                               // K <= 1024
+    const u64 s = wave_sort_desc(v, lane);
+    if (lane == q - 1) wave_q[w] = s;
+    __syncthreads();
+    u64 t = wave_q[0];
+#pragma unroll
+    for (int i = 1; i < kKlThreads / 64; ++i) { const u64 o = wave_q[i]; t = o < t ? o : t; }
+    return t;
+}
 }  // namespace
 
 // Stage 1 of the selection, one workgroup per (slice g of the vocabulary, event e): the keys of the
@@ -121,6 +137,7 @@ kl_select_slices_kernel(const float* __restrict__ z_target, int V, int K, int G,
     __shared__ u64 cand[kKlCand];
     __shared__ int ncand;
     __shared__ u64 prefix_s;
+    __shared__ u64 wave_q[kKlThreads / 64];
     __shared__ int need_s, done_s;
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -148,8 +165,8 @@ kl_select_slices_kernel(const float* __restrict__ z_target, int V, int K, int G,
         for (int i = lo + tid; i < hi; i += kKlThreads) { mx = fmaxf(mx, z[i]); any = true; }
     }
     // (absent threads contribute 0, below every real value)
-    const u64 kth = kth_largest_1024(any ? (u64)f32_to_ordered(mx) << 32 : 0ull, Kl, 32, hist, &prefix_s, &need_s);
-    const float tau0 = kth ? ordered_to_f32((uint32_t)(kth >> 32)) : -INFINITY;   // fewer than Kl threads saw a logit: keep all
+    const u64 kth = kth_bound_1024(any ? (u64)f32_to_ordered(mx) << 32 : 0ull, Kl, wave_q);
+    const float tau0 = kth ? ordered_to_f32((uint32_t)(kth >> 32)) : -INFINITY;   // too few threads saw a logit: keep all
     auto consider = [&](float v, int i) {
         if (v >= tau0) {
             const int p = atomicAdd(&ncand, 1);
