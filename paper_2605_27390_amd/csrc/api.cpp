@@ -146,7 +146,7 @@ int evospec_active_lmhead_partials(const void* h, int M, int d, const void* W_ac
     int num_cu = 0;
     rc = device_num_cu(&num_cu);
     if (rc) return rc;
-    const Plan p = make_plan(M, V_act, k, num_cu);
+    const Plan p = make_plan(M, V_act, d, k, num_cu);
     char* ws = static_cast<char*>(workspace);
     hipError_t e = launch_partials(p, h, M, d, W_act, ids, V_act, k, ws + p.keys_off, ws + p.stats_off,
                                    static_cast<hipStream_t>(stream), layout == EVOSPEC_PACKED);
@@ -165,7 +165,7 @@ int evospec_active_lmhead_merge(int M, int V_act, int d, int k, float* out_vals,
     int num_cu = 0;
     int rc = device_num_cu(&num_cu);
     if (rc) return rc;
-    const Plan p = make_plan(M, V_act, k, num_cu);
+    const Plan p = make_plan(M, V_act, d, k, num_cu);
     const char* ws = static_cast<const char*>(workspace);
     MergeSet a{ws + p.keys_off, ws + p.stats_off, p.n_slabs, 0, kMTile};
     MergeSet none{};
@@ -207,7 +207,7 @@ int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids
     }
     for (int m0 = 0; m0 < M; m0 += kMTile) {            // passes of 64 draft rows share the scratch
         const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
-        const Plan p = make_plan(rows, V_act, k, num_cu);
+        const Plan p = make_plan(rows, V_act, d, k, num_cu);
         hipError_t e = launch_partials(p, hp + (size_t)m0 * d, rows, d, W_act, ids, V_act, k,
                                        ws + p.keys_off, ws + p.stats_off, st, packed);
         if (e != hipSuccess) return hip_fail(e);
@@ -294,7 +294,7 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
         if (e != hipSuccess) return hip_fail(e);
         core = MergeSet{ws + gp.keys_off, ws + gp.stats_off, gp.n_slabs, 0, M, gp.list_len, true};
     } else if (V_core > 0) {
-        const Plan pc = make_plan(kMTile, V_core, k, num_cu);
+        const Plan pc = make_plan(kMTile, V_core, d, k, num_cu);
         for (int m0 = 0, pss = 0; m0 < M; m0 += kMTile, ++pss) {
             const int rows = (M - m0) < kMTile ? (M - m0) : kMTile;
             char* w = ws + (size_t)pss * core_stride;
@@ -316,7 +316,7 @@ int evospec_active_lmhead_topk_segmented(const void* h, int M, int d, const void
         for (int i = 0; i < cb.n; ++i) max_rows = cb.rows[i] > max_rows ? cb.rows[i] : max_rows;
         MergeSet arc{};
         if (V_arc > 0) {
-            const Plan pa = make_plan(max_rows, V_arc, k, num_cu, cb.n);
+            const Plan pa = make_plan(max_rows, V_arc, d, k, num_cu, cb.n);
             BatchLayout bl;
             bl.seq_rows = V_arc;
             bl.chunk_bytes = arc_stride;

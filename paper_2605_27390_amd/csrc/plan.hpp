@@ -18,6 +18,7 @@ constexpr int kKC = 256;            // hidden-dimension chunk staged in LDS per 
 constexpr int kHStride = kKC + 8;   // LDS row stride of the h chunk (bf16 elements, +16 B pad)
 constexpr int kRowsMinSlab = 64;    // smallest slab any plan uses (workspace upper bound)
 constexpr int kLdsLimit = 160 * 1024;
+constexpr int kRoundRows = 37;      // fixed cost of a round of workgroups, in slab rows (see make_plan)
 
 // Slab shapes that have a compiled kernel: X(nw, rgw, rc) with nw wavefronts per workgroup, rgw
 // 16-row groups per wavefront (RT = 16 * nw * rgw rows per slab) and a W-operand ring of rc chunks
@@ -114,9 +115,14 @@ inline size_t lds_bytes_for(int nw, int rgw, int mb) {
     return align_up(u, 16) + gm + wsum + small;
 }
 
-// Slab shape for V_act rows on a device with `num_cu` compute units: fewest row-rounds
-// (ceil(slabs / CUs) * RT); ties go to the larger slab (fewer partials to merge).
-inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, int k, int num_cu,
+// Slab shape for V_act rows of d elements on a device with `num_cu` compute units: the least
+// ceil(slabs / CUs) * (RT + kRoundRows), a round of workgroups costing its rows plus a fixed part
+// (first loads, epilogue: about what 37 rows of 8 KiB take to stream into one CU); ties go to the
+// larger slab (fewer partials to merge).  A slab
+// whose bytes are a multiple of 1 MiB is charged one eighth more: all workgroups then walk through
+// memory at the same offset within a MiB and meet at the same memory channels (measured on MI355X
+// at 32,256 x 4,096: 8 wavefronts = 1 MiB slabs 59 us, 9 wavefronts on fewer CUs 56 us).
+inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, int d, int k, int num_cu,
                       int replicas = 1 /*chunks that share the launch*/) {
     Plan best;
     long best_cost = -1;
@@ -128,7 +134,8 @@ inline Plan make_plan(int rows /*draft rows in this pass, 1..64*/, int V_act, in
         const size_t lds = lds_bytes_for(nw, rgw, mb);
         if (lds > (size_t)kLdsLimit) continue;
         const long rounds = ((long)n_slabs * replicas + num_cu - 1) / num_cu;
-        const long cost = rounds * rt;
+        long cost = rounds * (rt + kRoundRows) * 8;
+        if (((size_t)rt * (size_t)d * 2) % ((size_t)1 << 20) == 0) cost += cost / 8;
         if (best_cost < 0 || cost < best_cost || (cost == best_cost && rt > best.rt)) {
             best_cost = cost;
             best.nw = nw; best.rgw = rgw; best.rc = kShapes[i].rc; best.mb = mb; best.rt = rt; best.n_slabs = n_slabs;
