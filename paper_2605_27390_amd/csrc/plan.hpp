@@ -30,6 +30,12 @@ struct SlabShape { int nw; int rgw; int rc; };
 constexpr SlabShape kShapes[] = {EVOSPEC_SLAB_SHAPES(EVOSPEC_SHAPE_ENTRY)};
 #undef EVOSPEC_SHAPE_ENTRY
 constexpr int kNumShapes = sizeof(kShapes) / sizeof(kShapes[0]);
+constexpr bool shapes_respect_min_slab() {
+    for (int i = 0; i < kNumShapes; ++i)
+        if (16 * kShapes[i].nw * kShapes[i].rgw < kRowsMinSlab) return false;
+    return true;
+}
+static_assert(shapes_respect_min_slab(), "workspace_upper_bound assumes no slab below kRowsMinSlab rows");
 
 // A batch of independent problems handled by one launch (grid.y): chunk i is the draft rows
 // [m0, m0 + rows) of h against the rows of sequence `seq` of a per-sequence matrix.  For the
