@@ -50,7 +50,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU kernel path; --gpus must be 1 "
-              "(how the path would shard is described in DESIGN.md)", file=sys.stderr)
+              "(sharding over several GPUs is not part of it)", file=sys.stderr)
         return 2
 
     import numpy as np
