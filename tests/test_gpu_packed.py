@@ -328,3 +328,42 @@ def test_step_is_capturable_in_a_graph(ev, oracle_mod):
         torch.cuda.synchronize()
         assert torch.equal(ov, want[0]) and torch.equal(oi, want[1]) and torch.equal(ol, want[2]), f"replay {r}"
     assert np.array_equal(act.cpu().numpy(), ref_ids)
+
+
+def test_two_host_threads_on_their_own_streams(ev):
+    """The library keeps no per-call state: two host threads, each with its own stream, workspace and
+    outputs, can run heads on the same matrices at the same time (ctypes drops the GIL in a call)."""
+    import threading
+    import torch
+    W, h, ids = problem(4242, 3000, 512, 60)
+    P, idd = pack(ev, W), to_dev_i32(ids)
+    hs = [to_dev_bf16(h), to_dev_bf16(h[::-1].copy())]
+    k = 10
+    want = []
+    for t in range(2):
+        v, i, l = ev.active_lmhead_topk(hs[t], P, idd, k)
+        torch.cuda.synchronize()
+        want.append((v.clone(), i.clone(), l.clone()))
+    errors = []
+
+    def worker(t):
+        try:
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                ws = torch.empty(ev.workspace_bytes(60, 3000, 512, k), dtype=torch.uint8, device="cuda")
+                for _ in range(25):
+                    v, i, l = ev.active_lmhead_topk(hs[t], P, idd, k, workspace=ws)
+                    st.synchronize()
+                    if not (torch.equal(v, want[t][0]) and torch.equal(i, want[t][1]) and torch.equal(l, want[t][2])):
+                        errors.append(f"thread {t}: result differs")
+                        return
+        except Exception as exc:            # surfaced in the main thread
+            errors.append(f"thread {t}: {exc!r}")
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not any(th.is_alive() for th in threads), "a worker did not finish"
+    assert not errors, errors
