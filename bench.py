@@ -196,6 +196,15 @@ def main() -> int:
         # cache-warm figure (one copy), update kernels alone, and the unpruned head on the same GPU
         extra["head_us_cache_warm"] = round(timed(
             lambda i: ev.active_lmhead_topk(h, W_acts[0], act_ids[0], k, out_v, out_i, out_l, ws), n_ev), 2)
+        # a decode loop re-reads ONE W_act every step: the same kernel without the rotation over copies
+        # (part of the 302 MB then comes from the 256 MB memory-side cache, so this is not an HBM figure)
+        one_us = timed(lambda i: ev.active_lmhead_partials(h, W_acts[0], act_ids[0], k, ws), n_ev)
+        extra["single_copy"] = {"partials_us": round(one_us, 2),
+                                "bytes_per_s_over_hbm_peak": round(alg_bytes / one_us / 1e3 / HBM_PEAK_GBPS, 4)}
+        if upd_slots:
+            extra["single_copy"]["step_us"] = round(timed(
+                lambda i: ev.active_lmhead_topk_then_update(h, W_acts[0], act_ids[0], k, W_lm, upd_ids[0], upd_slots[0],
+                                                            out_v, out_i, out_l, ws), n_ev), 2)
         if upd_slots:
             extra["step_us_separate_calls"] = round(timed(step_separate, n_ev), 2)
             extra["gather32_us"] = round(timed(
