@@ -33,7 +33,7 @@
 extern "C" {
 #endif
 
-#define EVOSPEC_VERSION 200
+#define EVOSPEC_VERSION 210
 #define EVOSPEC_K_MAX 64        /* largest k of the fused top-k                         */
 #define EVOSPEC_M_TILE 64       /* draft rows handled by one pass over W_act            */
 
@@ -47,7 +47,9 @@ typedef enum evospec_status {
     EVOSPEC_BAD_SEGMENTS = 6,       /* row_off not monotone, row_off[0]!=0, row_off[S]!=M */
     EVOSPEC_INVALID_IDS = 7,        /* evospec_validate_ids only                          */
     EVOSPEC_HIP_ERROR = 8,          /* a launch failed; text via evospec_last_hip_error() */
-    EVOSPEC_BAD_LAYOUT = 9          /* layout is neither EVOSPEC_ROW_MAJOR nor EVOSPEC_PACKED */
+    EVOSPEC_BAD_LAYOUT = 9,         /* layout is neither EVOSPEC_ROW_MAJOR nor EVOSPEC_PACKED */
+    EVOSPEC_STATIC_SCRATCH_EXCEEDED = 10 /* evospec_active_lmhead_topk_static: the shapes need more
+                                            scratch than EVOSPEC_STATIC_SCRATCH_BYTES             */
 } evospec_status;
 
 /*
@@ -127,6 +129,28 @@ int evospec_active_lmhead_topk(const void *h, int M, int d,
                                const void *W_act, const int32_t *ids, int V_act, int layout, int k,
                                float *out_vals, int32_t *out_ids, float *out_logz,
                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * evospec_active_lmhead_topk for callers that cannot allocate device memory or carry a workspace
+ * around: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and kernels as evospec_active_lmhead_topk, except that the per-slab
+ * partial results live in a fixed device array inside the library (EVOSPEC_STATIC_SCRATCH_BYTES
+ * per GPU, held from the first call on that GPU until the process ends) instead of a caller
+ * workspace.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine)
+ * and does not synchronise; its first call on a device looks up that device's copy of the array.
+ * Shapes whose evospec_workspace_bytes(M, V_act, d, k) exceeds EVOSPEC_STATIC_SCRATCH_BYTES are
+ * rejected with EVOSPEC_STATIC_SCRATCH_EXCEEDED before anything is enqueued.  For M <= 128 the need
+ * is 8 (k + 1) bytes per active row: the limit covers V_act <= 95,325 at k = 10 and the full
+ * 151,936-row head up to k = 5; from 129 draft rows on the need also grows with M (136 bytes per
+ * draft row and 128 active rows at k <= 16) and only small problems fit.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or different threads without ordering) race on it; order them on one stream.  Nothing in
+ * the array has to start at a given value, so the contents a previous call left behind are harmless.
+ */
+#define EVOSPEC_STATIC_SCRATCH_BYTES (8u << 20)
+int evospec_active_lmhead_topk_static(const void *h, int M, int d,
+                                      const void *W_act, const int32_t *ids, int V_act, int layout, int k,
+                                      float *out_vals, int32_t *out_ids, float *out_logz, void *stream);
 
 /*
  * The two halves of evospec_active_lmhead_topk, exposed so that a caller (or a profiler)

@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     workspace_bytes_segmented,
     active_gather,
     active_lmhead_topk,
+    active_lmhead_topk_static,
+    STATIC_SCRATCH_BYTES,
     active_lmhead_topk_then_update,
     active_lmhead_partials,
     active_lmhead_merge,

@@ -17,7 +17,9 @@ M_TILE = 64
 STATUS = {
     0: "OK", 1: "NULL_POINTER", 2: "BAD_SHAPE", 3: "BAD_K", 4: "MISALIGNED",
     5: "WORKSPACE_TOO_SMALL", 6: "BAD_SEGMENTS", 7: "INVALID_IDS", 8: "HIP_ERROR", 9: "BAD_LAYOUT",
+    10: "STATIC_SCRATCH_EXCEEDED",
 }
+STATIC_SCRATCH_BYTES = 8 << 20
 ROW_MAJOR = 0
 PACKED = 1
 
@@ -56,6 +58,8 @@ def _load() -> ctypes.CDLL:
     L.evospec_active_gather.argtypes = [vp, ci, ci, vp, vp, ci, vp, vp, ci, ci, vp]
     L.evospec_active_lmhead_topk.restype = ci
     L.evospec_active_lmhead_topk.argtypes = [vp, ci, ci, vp, vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+    L.evospec_active_lmhead_topk_static.restype = ci
+    L.evospec_active_lmhead_topk_static.argtypes = [vp, ci, ci, vp, vp, ci, ci, ci, vp, vp, vp, vp]
     L.evospec_active_lmhead_topk_then_update.restype = ci
     L.evospec_active_lmhead_topk_then_update.argtypes = [vp, ci, ci, vp, vp, ci, ci, ci, vp, vp, vp, vp, sz,
                                                          vp, ci, vp, vp, ci, vp]
@@ -224,6 +228,16 @@ def active_lmhead_topk(h, W_act, ids, k, out_vals=None, out_ids=None, out_logz=N
                                           _ptr(out_vals), _ptr(out_ids), _ptr(out_logz),
                                           _ptr(workspace), workspace.numel(), _stream()),
            "evospec_active_lmhead_topk")
+    return out_vals, out_ids, out_logz
+
+
+def active_lmhead_topk_static(h, W_act, ids, k, out_vals, out_ids, out_logz):
+    """The restricted head on the library's own fixed scratch (no workspace, nothing allocated here
+    either: the caller passes the outputs)."""
+    M, d, V_act, layout = _head_shapes(h, W_act, ids)
+    _check(lib.evospec_active_lmhead_topk_static(_ptr(h), M, d, _ptr(W_act), _ptr(ids), V_act, layout, k,
+                                                 _ptr(out_vals), _ptr(out_ids), _ptr(out_logz), _stream()),
+           "evospec_active_lmhead_topk_static")
     return out_vals, out_ids, out_logz
 
 

@@ -81,6 +81,8 @@ const char* evospec_status_string(int status) {
         case EVOSPEC_INVALID_IDS: return "ids out of range or not unique";
         case EVOSPEC_HIP_ERROR: return "HIP error (see evospec_last_hip_error)";
         case EVOSPEC_BAD_LAYOUT: return "layout must be EVOSPEC_ROW_MAJOR or EVOSPEC_PACKED";
+        case EVOSPEC_STATIC_SCRATCH_EXCEEDED:
+            return "shapes need more scratch than EVOSPEC_STATIC_SCRATCH_BYTES (use the workspace variant)";
         default: return "unknown status";
     }
 }
@@ -175,7 +177,7 @@ int evospec_active_lmhead_merge(int M, int V_act, int d, int k, float* out_vals,
 
 }  // extern "C"
 
-namespace {
+namespace evospec {
 // The head, with an optional update that rides on its last merge launch.
 int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids,
               int V_act, int layout, int k, float* out_vals, int32_t* out_ids, float* out_logz,
@@ -218,7 +220,9 @@ int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids
     }
     return EVOSPEC_OK;
 }
-}  // namespace
+
+int record_hip_error(hipError_t e) { return hip_fail(e); }
+}  // namespace evospec
 
 extern "C" {
 

@@ -59,4 +59,12 @@ hipError_t launch_kl_gate(const float* z_target, int E, int V, const void* h_dra
                           void* workspace, hipStream_t stream);
 hipError_t run_validate_ids(const int32_t* ids, int n, int V, hipStream_t stream, int* bad);
 
+// The head behind evospec_active_lmhead_topk (api.cpp): validates, plans and launches on the given
+// scratch buffer; returns an evospec_status.  `update`, if given, rides on the last launch.
+int head_impl(const void* h, int M, int d, const void* W_act, const int32_t* ids, int V_act, int layout, int k,
+              float* out_vals, int32_t* out_ids, float* out_logz, void* workspace, size_t workspace_bytes,
+              void* stream, const GatherArgs* update);
+// Stores the text of a HIP error for evospec_last_hip_error() and returns EVOSPEC_HIP_ERROR.
+int record_hip_error(hipError_t e);
+
 }  // namespace evospec

@@ -32,11 +32,11 @@ def test_library_exports_every_declared_symbol(ev):
     assert len(syms) >= 11
     for s in syms:
         assert hasattr(ev.lib, s), f"{s} declared in include/ but not exported"
-    assert ev.version() == 200
+    assert ev.version() == 210
 
 
 def test_status_strings(ev):
-    for code in range(10):
+    for code in range(11):
         assert ev.status_string(code) and ev.status_string(code) != "unknown status"
     assert ev.status_string(99) == "unknown status"
 
@@ -111,6 +111,25 @@ def test_head_argument_errors_need_no_gpu(ev):
     assert g(al, 4, 64, al, None, 100, 2, 5, al, big, None) == 9                     # unknown layout
     assert f(al, 4, 64, al, None, 100, 7, 5, al, al, al, al, big, None) == 9
     assert f(al, 4, 64, al, None, 100, 1, 5, al, al, al, al, 16, None) == 5            # packed: same checks
+
+
+def test_static_scratch_entry_rejects_on_the_host(ev):
+    """The no-allocation variant: same argument checks as the workspace variant, and shapes whose
+    scratch need exceeds the fixed array are refused before any HIP call."""
+    L = ev.lib
+    buf = ctypes.create_string_buffer(4096 + 64)
+    al = ctypes.c_void_p((ctypes.addressof(buf) + 15) // 16 * 16)
+    f = L.evospec_active_lmhead_topk_static
+    assert f(al, 4, 60, al, None, 100, 0, 5, al, al, al, None) == 2
+    assert f(al, 4, 64, al, None, 100, 0, 0, al, al, al, None) == 3
+    assert f(al, 0, 64, al, None, 100, 0, 5, al, al, al, None) == 0             # M == 0: no-op
+    cap = ev.STATIC_SCRATCH_BYTES
+    assert ev.workspace_bytes(60, 36864, 4096, 10) <= cap                       # the headline shape fits
+    assert ev.workspace_bytes(60, 151936, 4096, 10) > cap
+    assert f(al, 60, 4096, al, None, 151936, 0, 10, al, al, al, None) == 10
+    assert ev.workspace_bytes(960, 36864, 4096, 10) > cap
+    assert f(al, 960, 4096, al, None, 36864, 0, 10, al, al, al, None) == 10
+    assert "EVOSPEC_STATIC_SCRATCH_BYTES" in ev.status_string(10)
 
 
 def test_gather_argument_errors_need_no_gpu(ev):
