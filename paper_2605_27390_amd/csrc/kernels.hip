@@ -164,9 +164,10 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
     extern __shared__ __align__(16) unsigned char smem[];
     // region U: h chunks during the contraction, the survivors' keys afterwards
     uint16_t* Hs = reinterpret_cast<uint16_t*>(smem);
-    u64* list = reinterpret_cast<u64*>(smem);                                 // [MR][RT]
+    u64* list = reinterpret_cast<u64*>(smem);                                 // [MR][LS]
+    constexpr int LS = list_stride(RT);
     constexpr size_t hs_bytes = 2ull * MR * kHStride * 2;
-    constexpr size_t list_bytes = (size_t)MR * RT * 8;
+    constexpr size_t list_bytes = (size_t)MR * list_stride(RT) * 8;
     constexpr size_t u_bytes = align_up(hs_bytes > list_bytes ? hs_bytes : list_bytes, 16);
     constexpr int NGS = 4 * NW;                                               // row stride of gm
     float* gm = reinterpret_cast<float*>(smem + u_bytes);                     // [MR][NGS] group maxima
@@ -436,7 +437,7 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
             base[mb] = pick[mb] ? atomicAdd(&cnt[mb * 16 + n16], __popc(pick[mb])) : 0;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            u64* dst = list + (size_t)(mb * 16 + n16) * RT + base[mb];
+            u64* dst = list + (size_t)(mb * 16 + n16) * LS + base[mb];
 #pragma unroll
             for (int rg = 0; rg < RGW; ++rg) {
                 const int idv[4] = {id4[rg].x, id4[rg].y, id4[rg].z, id4[rg].w};
@@ -455,7 +456,7 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
     if (tid < rows * NW) {
         const int m = tid / NW, sub = tid - m * NW;
         const int c = cnt[m];
-        const u64* lst = list + (size_t)m * RT;
+        const u64* lst = list + (size_t)m * LS;
         u64* outk = part_keys + ((size_t)blockIdx.x * kMTile + m) * k;
         for (int q = sub; q < c; q += NW) {
             const u64 mine = lst[q];

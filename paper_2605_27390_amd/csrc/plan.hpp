@@ -109,11 +109,16 @@ inline int group_level_for(int k, int nw) {
     return 0;
 }
 
+// Row stride, in keys, of the candidate lists of the slab epilogue: two keys of padding make the rows
+// start 16 bytes apart modulo the 64 LDS banks, so that accesses of the draft rows of a wavefront to
+// the same list position spread over all banks (a stride of rt keys maps every row to two banks).
+constexpr int list_stride(int rt) { return rt + 2; }
+
 inline size_t lds_bytes_for(int nw, int rgw, int mb) {
     const int rt = 16 * nw * rgw;
     const int mrows = 16 * mb;
     size_t hs = 2ull * mrows * kHStride * 2;                 // h chunk, double buffered
-    size_t list = (size_t)mrows * rt * 8;                    // surviving keys per draft row
+    size_t list = (size_t)mrows * list_stride(rt) * 8;       // surviving keys per draft row
     size_t u = hs > list ? hs : list;                        // the two never live together
     size_t gm = (size_t)mrows * 4 * nw * 4;                  // group maxima
     size_t wsum = (size_t)nw * mrows * 4;                    // per-wave sum-exp
