@@ -45,8 +45,8 @@ def main() -> int:
                     help="layout of the compact matrices W_act (the library's packed layout, or row-major)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also time the head at the paper's own active-set sizes (adds extra.sweep)")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip extra.sweep (the head at the paper's own active-set sizes)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU kernel path; --gpus must be 1 "
@@ -180,10 +180,14 @@ def main() -> int:
         "avg_kernel_us": round(part_us, 2),
         "algorithmic_bytes": alg_bytes,
     }
+    # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes recorded under profiles/ (a
+    # counter pass cannot run inside this process); not measured in this run, so the line says where it is from
     tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.config}.json")
     if os.path.exists(tfile):
         try:
-            roof["traffic"] = json.load(open(tfile)).get("bytes_per_launch")
+            tj = json.load(open(tfile))
+            roof["traffic"] = tj.get("bytes_per_launch")
+            roof["traffic_source"] = f"profiles/hbm_traffic_{args.config}.json: rocprofv3 --pmc passes of {tj.get('kernel')}, not this run"
         except Exception:
             pass
 
@@ -368,7 +372,7 @@ def main() -> int:
             extra["arc_manager"]["oracle_us_per_event"] = round((time.perf_counter() - t0) / 300 * 1e6, 2)
         del W_tmp, I_tmp
 
-    if args.sweep and args.config == "draft60":
+    if not args.no_sweep and not args.no_extras and args.config == "draft60":
         # the paper's own active-set sizes (Table 1 and the default setting), same rotation rule:
         # enough copies of W_act that the weights come from HBM
         sweep = []

@@ -53,6 +53,8 @@ void evospec_arc_default_config(evospec_arc_config *cfg);
 /* core_ids[n_core] (may be NULL when n_core == 0): ids of the static core, never admitted. */
 int evospec_arc_create(const evospec_arc_config *cfg, const int32_t *core_ids, int n_core, evospec_arc **out);
 void evospec_arc_destroy(evospec_arc *arc);
+/* The configuration the manager was created with. */
+int evospec_arc_get_config(const evospec_arc *arc, evospec_arc_config *out);
 
 /* `steps` >= 0 decoding steps have passed. */
 int evospec_arc_advance(evospec_arc *arc, int steps);
@@ -82,7 +84,8 @@ int evospec_arc_resident(const evospec_arc *arc, int32_t *out_slots, int32_t *ou
  * outgoing neighbours of the co-occurrence graph, given in CSR form (row_ptr[V + 1], col_idx; a
  * row lists successors by decreasing weight); duplicates keep their first place.  Order: seeds,
  * then successors seed by seed.  out[out_cap] receives at most out_cap ids, *n_out their number.
- * Seeds outside [0, V) are dropped.  Host pointers only.
+ * Seeds and successors outside [0, V) are dropped.  row_ptr / col_idx may be NULL when
+ * max_successors == 0 (no graph).  Host pointers only.
  */
 int evospec_form_candidates(const int32_t *target_top, int n_target, const int32_t *mips_top, int n_mips,
                             const int64_t *row_ptr, const int32_t *col_idx, int V, int max_successors,
@@ -99,9 +102,15 @@ int evospec_form_candidates(const int32_t *target_top, int n_target, const int32
  *   4. evospec_active_gather of the admitted (slot, id) pairs into W_act / act_ids.
  * h_target (bf16 [d]), W_lm (bf16 [V, d]), W_act (V_act rows in `layout`, see evospec.h), act_ids,
  * workspace are device pointers, 16-byte aligned; everything else is host memory.  The call WAITS for step 1 on `stream` (it needs the
- * ids on the host) and returns after the gather has been enqueued.  out_slots / out_ids (host,
- * max_insert entries each, may be NULL) receive the admitted pairs, *n_out their number.
+ * ids on the host), uploads the admitted pairs with copies that are complete when they return (so the
+ * next event may use any stream), and returns after the gather has been enqueued.  out_slots / out_ids
+ * (host, max_insert entries each, may be NULL) receive the admitted pairs, *n_out their number.
  * workspace_bytes must be at least evospec_path_a_workspace_bytes(V, d, n_mips, max_insert).
+ * All arguments, those of the final gather included (W_act, act_ids, layout, and V_act >= slot_base +
+ * capacity of the manager), are checked before the search is enqueued and before the manager admits
+ * anything: an argument error leaves the manager and the GPU untouched.  A HIP failure after the
+ * admission (a copy or launch that fails) leaves the manager ahead of W_act: rebuild W_act from
+ * evospec_arc_resident in that case.
  */
 int evospec_path_a_workspace_bytes(int V, int d, int n_mips, int max_insert, size_t *out_bytes);
 int evospec_path_a_event(evospec_arc *arc, const void *h_target, int d, const void *W_lm, int V,

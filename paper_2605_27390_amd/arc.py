@@ -21,6 +21,8 @@ lib.evospec_arc_create.restype = ctypes.c_int
 lib.evospec_arc_create.argtypes = [ctypes.POINTER(_Config), _i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p)]
 lib.evospec_arc_destroy.restype = None
 lib.evospec_arc_destroy.argtypes = [ctypes.c_void_p]
+lib.evospec_arc_get_config.restype = ctypes.c_int
+lib.evospec_arc_get_config.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Config)]
 lib.evospec_arc_advance.restype = ctypes.c_int
 lib.evospec_arc_advance.argtypes = [ctypes.c_void_p, ctypes.c_int]
 lib.evospec_arc_touch.restype = ctypes.c_int
@@ -123,12 +125,13 @@ def form_candidates(target_top, mips_top, row_ptr, col_idx, V, max_successors=8,
     """Ordered, de-duplicated candidate ids of one failure event (host arrays in, list out)."""
     t = np.ascontiguousarray(np.asarray(target_top, dtype=np.int32))
     m = np.ascontiguousarray(np.asarray(mips_top, dtype=np.int32))
-    rp = np.ascontiguousarray(np.asarray(row_ptr, dtype=np.int64))
-    ci = np.ascontiguousarray(np.asarray(col_idx, dtype=np.int32))
+    rp = None if row_ptr is None else np.ascontiguousarray(np.asarray(row_ptr, dtype=np.int64))
+    ci = None if col_idx is None else np.ascontiguousarray(np.asarray(col_idx, dtype=np.int32))
     out = np.empty(max(1, cap), dtype=np.int32)
     n = ctypes.c_int(0)
     _check(lib.evospec_form_candidates(_ptr(t) if t.size else None, int(t.size), _ptr(m) if m.size else None, int(m.size),
-                                       rp.ctypes.data_as(_i64p), _ptr(ci) if ci.size else None, int(V), int(max_successors),
+                                       None if rp is None else rp.ctypes.data_as(_i64p),
+                                       _ptr(ci) if ci is not None and ci.size else None, int(V), int(max_successors),
                                        _ptr(out), int(cap), ctypes.byref(n)), "evospec_form_candidates")
     return out[:n.value].tolist()
 

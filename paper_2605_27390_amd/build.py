@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libevospec.so")
-SOURCES = ["kernels.hip", "gemm.hip", "klgate.hip", "noalloc.hip", "api.cpp", "arc.cpp"]
+SOURCES = ["kernels.hip", "gemm.hip", "klgate.hip", "noalloc.hip", "api.cpp", "arc.cpp", "path_a.cpp"]
 HEADERS = ["plan.hpp", "launch.hpp", "common.hpp", os.path.join(ROOT, "include", "evospec.h"),
            os.path.join(ROOT, "include", "evospec_arc.h")]
 

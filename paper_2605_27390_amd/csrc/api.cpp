@@ -3,6 +3,7 @@
 // Nothing here allocates device memory or waits for the GPU (evospec_validate_ids aside).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 
@@ -23,16 +24,16 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // Compute units of the current device (cached per device id).
 int device_num_cu(int* out) {
-    static int cached[64] = {};
+    static std::atomic<int> cached[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e);
-    if (dev >= 0 && dev < 64 && cached[dev] > 0) { *out = cached[dev]; return EVOSPEC_OK; }
+    if (dev >= 0 && dev < 64 && cached[dev].load() > 0) { *out = cached[dev].load(); return EVOSPEC_OK; }
     int n = 0;
     e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return hip_fail(e);
     if (n <= 0) n = 256;
-    if (dev >= 0 && dev < 64) cached[dev] = n;
+    if (dev >= 0 && dev < 64) cached[dev].store(n);
     *out = n;
     return EVOSPEC_OK;
 }

@@ -6,8 +6,7 @@
 // Each of T1, T2, B1, B2 is an intrusive doubly linked list over one node pool (head = least
 // recently used); a hash map takes a token id to its node.  Every operation of an event is
 // O(1) except the search for a victim that is old enough, which walks past the young tokens.
-#include <hip/hip_runtime.h>
-
+// Nothing in this file touches the GPU: it builds with the host compiler alone.
 #include <cstdint>
 #include <new>
 #include <unordered_map>
@@ -45,7 +44,6 @@ struct evospec_arc {
     std::unordered_map<int32_t, int> index;       // token id -> node (resident or ghost)
     std::unordered_set<int32_t> core;
     std::unordered_set<int32_t> seen;
-    std::vector<int32_t> upload;                  // (slots | ids) of the last Path-A event: source of its host-to-device copies
 
     int alloc_node() {
         if (!free_nodes.empty()) { const int n = free_nodes.back(); free_nodes.pop_back(); return n; }
@@ -125,6 +123,12 @@ int evospec_arc_create(const evospec_arc_config* cfg, const int32_t* core_ids, i
 }
 
 void evospec_arc_destroy(evospec_arc* arc) { delete arc; }
+
+int evospec_arc_get_config(const evospec_arc* arc, evospec_arc_config* out) {
+    if (!arc || !out) return EVOSPEC_NULL_POINTER;
+    *out = arc->cfg;
+    return EVOSPEC_OK;
+}
 
 int evospec_arc_advance(evospec_arc* arc, int steps) {
     if (!arc) return EVOSPEC_NULL_POINTER;
@@ -253,93 +257,19 @@ int evospec_form_candidates(const int32_t* target_top, int n_target, const int32
     if (max_successors > 0 && (!row_ptr || !col_idx)) return EVOSPEC_NULL_POINTER;
     std::unordered_set<int32_t> seen;
     int n = 0, n_seeds = 0;
-    auto add = [&](int32_t x) {
-        if (n < out_cap && seen.insert(x).second) out[n++] = x;
+    auto add = [&](int32_t x) {                      // ids outside the vocabulary never become candidates
+        if (x >= 0 && x < V && n < out_cap && seen.insert(x).second) out[n++] = x;
     };
-    for (int i = 0; i < n_target; ++i)
-        if (target_top[i] >= 0 && target_top[i] < V) add(target_top[i]);
-    for (int i = 0; i < n_mips; ++i)
-        if (mips_top[i] >= 0 && mips_top[i] < V) add(mips_top[i]);
+    for (int i = 0; i < n_target; ++i) add(target_top[i]);
+    for (int i = 0; i < n_mips; ++i) add(mips_top[i]);
     n_seeds = n;
-    // (if the seeds alone fill `out`, there is no room for successors: nothing more to do)
-    for (int s = 0; s < n_seeds && n < out_cap; ++s) {
+    // (no successors asked for: the graph may be absent; seeds that fill `out` leave no room for any)
+    for (int s = 0; max_successors > 0 && s < n_seeds && n < out_cap; ++s) {
         const int64_t lo = row_ptr[out[s]], hi = row_ptr[out[s] + 1];
         for (int64_t j = lo; j < hi && j < lo + max_successors; ++j) add(col_idx[j]);
     }
     *n_out = n;
     return EVOSPEC_OK;
-}
-
-namespace {
-constexpr size_t kAlign = 256;
-size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
-constexpr int kMaxCandidates = 4096;
-}  // namespace
-
-int evospec_path_a_workspace_bytes(int V, int d, int n_mips, int max_insert, size_t* out_bytes) {
-    if (!out_bytes) return EVOSPEC_NULL_POINTER;
-    if (max_insert < 0) return EVOSPEC_BAD_SHAPE;
-    size_t head = 0;
-    const int rc = evospec_workspace_bytes(1, V, d, n_mips, &head);
-    if (rc) return rc;
-    // head scratch | top values, ids, log-normaliser of the search | slots, ids of the update
-    *out_bytes = up(head) + up((size_t)n_mips * 8 + 4) + up((size_t)max_insert * 8 + 8);
-    return EVOSPEC_OK;
-}
-
-int evospec_path_a_event(evospec_arc* arc, const void* h_target, int d, const void* W_lm, int V,
-                         const int32_t* target_top, int n_target, int n_mips,
-                         const int64_t* row_ptr, const int32_t* col_idx, int max_successors,
-                         void* W_act, int32_t* act_ids, int V_act, int layout,
-                         void* workspace, size_t workspace_bytes, void* stream,
-                         int32_t* out_slots, int32_t* out_ids, int* n_out) {
-    if (!arc || !n_out || !workspace) return EVOSPEC_NULL_POINTER;
-    if (n_mips < 1 || n_mips > EVOSPEC_K_MAX) return EVOSPEC_BAD_K;
-    if (n_target < 0 || (n_target > 0 && !target_top)) return n_target < 0 ? EVOSPEC_BAD_SHAPE : EVOSPEC_NULL_POINTER;
-    size_t need = 0;
-    int rc = evospec_path_a_workspace_bytes(V, d, n_mips, arc->cfg.max_insert, &need);
-    if (rc) return rc;
-    if (workspace_bytes < need) return EVOSPEC_WORKSPACE_TOO_SMALL;
-    size_t head = 0;
-    evospec_workspace_bytes(1, V, d, n_mips, &head);
-    char* ws = static_cast<char*>(workspace);
-    float* top_vals = reinterpret_cast<float*>(ws + up(head));
-    int32_t* top_ids = reinterpret_cast<int32_t*>(top_vals + n_mips);
-    float* top_logz = reinterpret_cast<float*>(top_ids + n_mips);
-    int32_t* upd = reinterpret_cast<int32_t*>(ws + up(head) + up((size_t)n_mips * 8 + 4));
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
-    // 1. exact search over the full vocabulary (identity ids), ids to the host
-    rc = evospec_active_lmhead_topk(h_target, 1, d, W_lm, nullptr, V, EVOSPEC_ROW_MAJOR, n_mips, top_vals, top_ids, top_logz,
-                                    workspace, head, stream);
-    if (rc) return rc;
-    int32_t mips[EVOSPEC_K_MAX];
-    if (hipMemcpyAsync(mips, top_ids, (size_t)n_mips * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
-        hipStreamSynchronize(st) != hipSuccess)
-        return EVOSPEC_HIP_ERROR;
-    // 2. candidates, 3. admission
-    std::vector<int32_t> cand((size_t)kMaxCandidates);
-    int n_cand = 0;
-    rc = evospec_form_candidates(target_top, n_target, mips, n_mips, row_ptr, col_idx, V, max_successors,
-                                 cand.data(), kMaxCandidates, &n_cand);
-    if (rc) return rc;
-    const int cap = arc->cfg.max_insert;
-    std::vector<int32_t>& pairs = arc->upload;    // outlives the asynchronous copies below
-    pairs.assign((size_t)2 * (cap > 0 ? cap : 1), 0);
-    int n_ins = 0;
-    rc = evospec_arc_event(arc, cand.data(), n_cand, pairs.data(), pairs.data() + cap, &n_ins);
-    if (rc) return rc;
-    *n_out = n_ins;
-    for (int i = 0; i < n_ins; ++i) {
-        if (out_slots) out_slots[i] = pairs[i];
-        if (out_ids) out_ids[i] = pairs[cap + i];
-    }
-    if (n_ins == 0) return EVOSPEC_OK;
-    // 4. the admitted rows into the compact matrix
-    if (hipMemcpyAsync(upd, pairs.data(), (size_t)n_ins * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
-        hipMemcpyAsync(upd + cap, pairs.data() + cap, (size_t)n_ins * 4, hipMemcpyHostToDevice, st) != hipSuccess)
-        return EVOSPEC_HIP_ERROR;
-    return evospec_active_gather(W_lm, V, d, upd + cap, upd, n_ins, W_act, act_ids, V_act, layout, stream);
 }
 
 }  // extern "C"

@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include <type_traits>
 
 #include "common.hpp"
@@ -511,17 +513,17 @@ hipError_t launch_gemm_partials(const void* h, int M, int d, const void* W, cons
     if (d % (2 * kGK) != 0 || d < 2 * kGK) return hipErrorInvalidValue;      // callers route such d elsewhere
     auto kern = packed ? lmhead_gemm_kernel<true> : lmhead_gemm_kernel<false>;
     constexpr int kMaxDevices = 64;
-    static bool attr_set[kMaxDevices] = {};
+    static std::atomic<bool> attr_set[kMaxDevices] = {};      // concurrent first calls may both set the (idempotent) attribute
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev]) {
+    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev].load(std::memory_order_acquire)) {
         for (auto kf : {lmhead_gemm_kernel<true>, lmhead_gemm_kernel<false>}) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(kf),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGLdsTotal);
             if (e != hipSuccess) return e;
         }
-        if (dev >= 0 && dev < kMaxDevices) attr_set[dev] = true;
+        if (dev >= 0 && dev < kMaxDevices) attr_set[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(v_tiles * m_tiles), dim3(256), kGLdsTotal, stream,
                        static_cast<const uint16_t*>(h), M, d, static_cast<const uint16_t*>(W), ids, V_act, k, gemm_list_len(k),

@@ -9,6 +9,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include <type_traits>
 
 #include "common.hpp"
@@ -679,15 +682,15 @@ hipError_t launch_partials_k(const Plan& p, const void* h, const ChunkBatch& cb,
                              const void* W, const int32_t* ids, int V_act, int k, void* keys, void* stats,
                              hipStream_t stream) {
     auto kern = lmhead_partials_kernel<NW, RGW, RC, MB, FULLK, PACKED>;
-    static bool attr_set[kMaxDevices] = {};
+    static std::atomic<bool> attr_set[kMaxDevices] = {};      // concurrent first calls may both set the (idempotent) attribute
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev]) {
+    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev].load(std::memory_order_acquire)) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit);
         if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < kMaxDevices) attr_set[dev] = true;
+        if (dev >= 0 && dev < kMaxDevices) attr_set[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(p.n_slabs, cb.n), dim3(NW * 64), p.lds_bytes, stream,
                        static_cast<const uint16_t*>(h), cb, bl.seq_rows, bl.chunk_bytes / 8, bl.chunk_bytes / 8, d,
@@ -807,6 +810,9 @@ hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids,
 }
 
 hipError_t run_validate_ids(const int32_t* ids, int n, int V, hipStream_t stream, int* bad) {
+    // one flag per device: calls from several threads take turns (the call waits for its kernel anyway)
+    static std::mutex flag_mutex;
+    std::lock_guard<std::mutex> lock(flag_mutex);
     int* flag = nullptr;
     hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&flag), HIP_SYMBOL(g_validate_flag));
     if (e != hipSuccess) return e;

@@ -94,3 +94,23 @@ def test_candidate_formation_matches_the_oracle():
     assert ev.form_candidates([2, 0], [0, 3], rp, ci, 10, 2) == [2, 0, 3, 6, 5, 1]
     # seeds outside the vocabulary are dropped
     assert ev.form_candidates([2, 10, -1], [3], rp, ci, 10, 0) == [2, 3]
+    # no successors asked for: the graph may be absent altogether
+    assert ev.form_candidates([2, 0], [0, 3], None, None, 10, 0) == [2, 0, 3]
+    L = ev.lib
+    n = ctypes.c_int(0)
+    seeds = (ctypes.c_int32 * 2)(2, 0)
+    out = (ctypes.c_int32 * 8)()
+    assert L.evospec_form_candidates(seeds, 2, None, 0, None, None, 10, 0, out, 8, ctypes.byref(n)) == 0 and n.value == 2
+    assert L.evospec_form_candidates(seeds, 2, None, 0, None, None, 10, 3, out, 8, ctypes.byref(n)) == 1   # graph needed
+    # successors outside the vocabulary never become candidates (they could not be gathered)
+    ci_bad = np.array([5, 60, -7, 6, 0, 9, 8, 1], dtype=np.int32)
+    assert ev.form_candidates([0], [], rp, ci_bad, 10, 3) == [0, 5]
+
+
+def test_get_config_round_trip(ArcManager):
+    import paper_2605_27390_amd as ev
+    m = ArcManager(capacity=16, p0=3, ghost_cap=5, max_insert=4, min_residency=2, warmup_events=0, slot_base=7)
+    cfg = ev.arc._Config()
+    assert ev.lib.evospec_arc_get_config(ctypes.c_void_p(m._h) if not isinstance(m._h, ctypes.c_void_p) else m._h, ctypes.byref(cfg)) == 0
+    assert (cfg.capacity, cfg.p0, cfg.ghost_capacity, cfg.max_insert, cfg.min_residency, cfg.warmup_events, cfg.slot_base) == (16, 3, 5, 4, 2, 0, 7)
+    assert ev.lib.evospec_arc_get_config(None, ctypes.byref(cfg)) == 1

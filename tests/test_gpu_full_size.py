@@ -1,6 +1,7 @@
 """GPU parity at the benchmark's full sizes (Qwen3-8B / EAGLE-2 shapes), in the launch
 configuration bench.py times.  The oracle computes every logit at these sizes in seconds on the
-host cores (OpenMP), except for the batched case, where it checks a sample of rows per sequence."""
+host cores (OpenMP): every row of every configuration is checked against it (the batched case on all
+960 rows in the packed layout, which bench.py times, and on a sample of rows per sequence in the other)."""
 import numpy as np
 import pytest
 
@@ -120,7 +121,8 @@ def test_full_vocabulary_head(ev, oracle_mod, lm_head):
 @pytest.mark.parametrize("layout", ["packed", "row_major"])
 def test_batched_serving(ev, oracle_mod, lm_head, layout):
     """Config 5: 16 sequences x 60 rows, shared 32,768-id core + 2,048 ARC ids per sequence.
-    The oracle checks 4 rows of every sequence (first, last and two inside)."""
+    Packed layout: the oracle checks all 960 rows.  Row-major: 4 rows of every sequence (first, last
+    and two inside) and id membership for the rest."""
     import torch
     W_bits, W_lm = lm_head
     c = gi.CONFIGS["batched"]
@@ -144,7 +146,7 @@ def test_batched_serving(ev, oracle_mod, lm_head, layout):
     assert np.isfinite(v).all() and np.isfinite(l).all() and (i >= 0).all()
     for s in range(S):
         union = np.concatenate([core, arcs[s]])
-        rows = row_off[s] + np.array([0, 17, 41, rps - 1])
+        rows = row_off[s] + (np.arange(rps) if layout == "packed" else np.array([0, 17, 41, rps - 1]))
         z = oracle_mod.logits(h[rows], W_bits[union])
         check_head(v[rows], i[rows], l[rows], z, union, k, f"batched seq {s}")
         # every returned id of the sequence's other rows is at least a member of its own union
@@ -153,15 +155,22 @@ def test_batched_serving(ev, oracle_mod, lm_head, layout):
         assert member[i[row_off[s]:row_off[s + 1]]].all()
 
 
-@pytest.mark.parametrize("shape", [s for s in gi.SWEEP if s[1] == 4096 and s[0] in
-                                   ("default_32000+256", "8k+256", "16k+1024")], ids=lambda s: s[0])
-def test_paper_active_set_sizes(ev, oracle_mod, lm_head, shape):
-    layout = "packed"
-    """The active-set sizes of the paper's own experiments (Table 1 and the default setting):
-    gather + head against the oracle on every logit."""
+@pytest.fixture(scope="module")
+def lm_head_d2048():
+    """The second synthetic LM head of the sweep (128,256 x 2,048 bf16, its own seed stream)."""
+    bits = gi.gen_W_lm(128256, 2048, gi.SEED_W + 1)
+    return bits, to_dev_bf16(bits)
+
+
+@pytest.mark.parametrize("shape", gi.SWEEP, ids=lambda s: s[0])
+def test_paper_active_set_sizes(ev, oracle_mod, lm_head, lm_head_d2048, shape):
+    """The active-set sizes of the paper's own experiments (Table 1 and the default setting) and the
+    d = 2048 shape: gather + head against the oracle on every logit, in the layout bench.py times."""
     import torch
-    W_bits, W_lm = lm_head
+    layout = "packed"
     name, d, V, n_core, n_arc, M, k = shape
+    W_bits, W_lm = lm_head if d == 4096 else lm_head_d2048
+    assert W_bits.shape == (V, d)
     core, arc = gi.core_arc_ids(V, n_core, n_arc, gi.SEED_IDS + 40)
     ids = np.concatenate([core, arc])
     h = gi.gen_h(M, d, gi.SEED_H + 60)
