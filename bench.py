@@ -45,9 +45,17 @@ def main() -> int:
                     help="layout of the compact matrices W_act (the library's packed layout, or row-major)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--extras", default="all",
+                    help="comma list of extra sections to run: core,depth,batched,host,sweep (default all); "
+                         "a profiler run names the one it wants")
     ap.add_argument("--no-sweep", action="store_true",
                     help="skip extra.sweep (the head at the paper's own active-set sizes)")
     args = ap.parse_args()
+    sections = {"core", "depth", "batched", "host", "sweep"} if args.extras == "all" else set(args.extras.split(","))
+    if args.no_extras:
+        sections = set()
+    if args.no_sweep:
+        sections.discard("sweep")
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU kernel path; --gpus must be 1 "
               "(sharding over several GPUs is not part of it)", file=sys.stderr)
@@ -196,7 +204,7 @@ def main() -> int:
              "rows_per_s": round(M / (us_step * 1e-6), 1),
              "hbm_gbps_step": round(alg_bytes / us_step / 1e3, 1),
              "hbm_frac_step": round(alg_bytes / us_step / 1e3 / HBM_PEAK_GBPS, 4)}
-    if not args.no_extras and args.config == "draft60":
+    if "core" in sections and args.config == "draft60":
         # cache-warm figure (one copy), update kernels alone, and the unpruned head on the same GPU
         extra["head_us_cache_warm"] = round(timed(
             lambda i: ev.active_lmhead_topk(h, W_acts[0], act_ids[0], k, out_v, out_i, out_l, ws), n_ev), 2)
@@ -255,6 +263,7 @@ def main() -> int:
         extra["fullvocab_head_us_packed"] = round(full_p_us, 2)
         extra["speedup_vs_fullvocab_packed"] = round(full_p_us / head_us, 3)
         del ws_full, W_full_p, ids_full
+    if "depth" in sections and args.config == "draft60":
         # per-depth tree expansion: 16,384 core + 2,048 ARC ids, M in {1, 4, 8}, and a 256-row update
         cd = gi.CONFIGS["depth"]
         ids_d = gi.active_ids("depth")
@@ -277,6 +286,7 @@ def main() -> int:
             depth[f"hbm_gbps_M{Md}"] = round(algorithmic_bytes(Vd, d, Md, k) / us / 1e3, 1)
         extra["depth_V18432"] = depth
         del Wd, idd
+    if "batched" in sections and args.config == "draft60":
         # batched serving: 16 sequences x 60 rows, shared 32,768-id core + 2,048 ARC ids per sequence
         cb = gi.CONFIGS["batched"]
         core_b, arcs_b = gi.batched_ids(V, cb["n_core"], cb["n_arc"], cb["S"])
@@ -301,7 +311,7 @@ def main() -> int:
                                  "rows_per_s": round(Mb / (seg_us * 1e-6), 1)}
         del W_core, W_arc, ws_b
 
-    if not args.no_extras and args.config == "draft60":
+    if "host" in sections and args.config == "draft60":
         # the step before the path: the C++ dynamic-buffer manager (paper defaults) on a stream of
         # failure events with Zipf-distributed candidates (20 seeds + up to 8 successors each, as
         # the appendix forms them), and the gather it drives with its own update sizes
@@ -372,7 +382,7 @@ def main() -> int:
             extra["arc_manager"]["oracle_us_per_event"] = round((time.perf_counter() - t0) / 300 * 1e6, 2)
         del W_tmp, I_tmp
 
-    if not args.no_sweep and not args.no_extras and args.config == "draft60":
+    if "sweep" in sections and args.config == "draft60":
         # the paper's own active-set sizes (Table 1 and the default setting), same rotation rule:
         # enough copies of W_act that the weights come from HBM
         sweep = []

@@ -33,16 +33,8 @@ constexpr int kKlBits = 11;
 constexpr int kKlBins = 1 << kKlBits;
 constexpr int kKlCand = 2048;                 // candidates the common path can rank
 
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-    return x;
-}
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    return x;
-}
+__device__ __forceinline__ float wave_sum(float x) { return evospec::wave_sum(x, (int)(threadIdx.x & 63)); }
+__device__ __forceinline__ float wave_max(float x) { return evospec::wave_max(x, (int)(threadIdx.x & 63)); }
 
 // Wave 0 only: the bin (from the top) in which the cumulative count of hist reaches `need`;
 // the number of entries in higher bins goes to *above_out, the bin's own count to *count (set by
