@@ -513,17 +513,20 @@ lmhead_partials_kernel(const uint16_t* __restrict__ h_all, ChunkBatch cb, int se
         const int c = cnt[m];
         const u64* lst = list + (size_t)m * LS;
         u64* outk = part_keys + ((size_t)blockIdx.x * kMTile + m) * k;
-        for (int q = sub; q < c; q += NW) {
-            const u64 mine = lst[q];
-            int rank = 0;
+        for (int q = sub; q < c; q += 2 * NW) {              // two candidates per pass share the reads of the list
+            const bool two = q + NW < c;
+            const u64 mine0 = lst[q], mine1 = two ? lst[q + NW] : ~0ull;
+            int rank0 = 0, rank1 = 0;
             int j = 0;
             for (; j + 4 <= c; j += 4) {
                 const ulonglong2 a = *reinterpret_cast<const ulonglong2*>(lst + j);
                 const ulonglong2 b2 = *reinterpret_cast<const ulonglong2*>(lst + j + 2);
-                rank += (a.x > mine) + (a.y > mine) + (b2.x > mine) + (b2.y > mine);
+                rank0 += (a.x > mine0) + (a.y > mine0) + (b2.x > mine0) + (b2.y > mine0);
+                rank1 += (a.x > mine1) + (a.y > mine1) + (b2.x > mine1) + (b2.y > mine1);
             }
-            for (; j < c; ++j) rank += lst[j] > mine;
-            if (rank < k) outk[rank] = mine;
+            for (; j < c; ++j) { const u64 o = lst[j]; rank0 += o > mine0; rank1 += o > mine1; }
+            if (rank0 < k) outk[rank0] = mine0;
+            if (two && rank1 < k) outk[rank1] = mine1;
         }
         if (sub == 0) {
             for (int j = c; j < k; ++j) outk[j] = 0;               // slab holds fewer than k rows
