@@ -5,19 +5,23 @@
 // when D_KL(p || q) exceeds the gate.
 //
 // Four launches:
-//  1. kl_select_slices_kernel, one workgroup of 16 wavefronts per (eighth of the vocabulary, event):
-//     every thread takes the maximum of its share of the slice; a value that K of these 1024 maxima
-//     reach (from one sort per wavefront) is a lower bound of the slice's K-th largest logit, so the
-//     logits that reach it (a few hundred) go to the workspace as 64-bit (logit, id) keys.  If more than 2048 reach it (masses
-//     of equal logits), radix select on the key instead (11 bits per pass, histogram in LDS, a pass
-//     is skipped as soon as the bin that holds the K-th key is taken whole) leaves exactly K;
-//  2. kl_select_final_kernel, one workgroup per event: the same bound over the slices' candidates,
-//     the survivors ranked by counting: the support, by decreasing key;
+//  1. kl_select_slices_kernel, one workgroup of 16 wavefronts per (eighth of the vocabulary, event),
+//     two of them per compute unit: every thread loads its share of the slice once (all requests in
+//     flight together, the values stay in registers) and takes its maximum; a value that K of these
+//     1024 maxima reach (the q-th largest of every wavefront, found bit by bit) is a lower bound of the
+//     slice's K-th largest logit, so the logits that reach it (a few hundred) go to the workspace as
+//     64-bit (logit, id) keys.  If more than 2048 reach it (masses of equal logits), radix select on
+//     the key instead (11 bits per pass, histogram in LDS, a pass is skipped as soon as the bin that
+//     holds the K-th key is taken whole) leaves exactly K;
+//  2. kl_select_final_kernel, one workgroup per event: the exact K-th largest of the per-thread
+//     maxima of the slices' candidates (a bitonic sort over the workgroup) bounds the answer, the
+//     survivors (a few more than K) are ranked by counting: the support, by decreasing key;
 //  3. kl_draft_logits_kernel, one workgroup of 4 wavefronts per 16 support rows of an event, so that
 //     the E x K rows of W_LM (the bulk of the bytes) are spread over the whole GPU: a wavefront
 //     takes 4 rows at a time, 16 bytes per lane and load, h in LDS;
 //  4. kl_divergence_kernel, one wavefront per event: log-sum-exp of both logit vectors and D_KL.
-// Latency bound: per event the target logits are read twice (they stay in L2) and K rows of W_LM once.
+// Bytes per event: the target logits once, K rows of W_LM once.  Stages 1 and 2 are bound by
+// latencies and by instruction issue on the few compute units they occupy, stage 3 by HBM.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -70,51 +74,91 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, int lane, int nee
     }
 }
 
-// The K-th largest (counting repeats) of the 1024 values v, one per thread, by radix select on
-// their top `bits` bits (the rest must be zero); every thread of the workgroup calls it.
-__device__ __forceinline__ u64 kth_largest_1024(u64 v, int K, int bits, uint32_t* hist, u64* prefix_s, int* need_s) {
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    if (tid == 0) { *prefix_s = 0; *need_s = K; }
-    int done = 0;
-    while (done < bits) {
-        const int nb = bits - done < kKlBits ? bits - done : kKlBits;
-        const int shift = 64 - done - nb;
-        for (int i = tid; i < kKlBins; i += kKlThreads) hist[i] = 0;
-        __syncthreads();
-        const u64 prefix = *prefix_s;
-        if (done == 0 || (v >> (64 - done)) == (prefix >> (64 - done)))
-            atomicAdd(&hist[(uint32_t)(v >> shift) & ((1u << nb) - 1u)], 1u);
-        __syncthreads();
-        if (w == 0) {
-            int bin = 0, above = 0, count = 0;
-            const int need = *need_s;
-            find_bin(hist, lane, need, &bin, &above, &count);
-            if (count > 0) {
-                *prefix_s = prefix | ((u64)bin << shift);
-                // 0: the whole bin is taken and the value bits are resolved, so the bound cannot loosen: stop
-                *need_s = (count == need - above && done + nb >= 32) ? 0 : need - above;
-            }
-        }
-        __syncthreads();
-        done += nb;
-        if (*need_s == 0) break;                                 // (prefix with zero low bits bounds exactly K values)
+// Sorting networks over 32-bit or 64-bit keys (T = uint32_t or u64), one key per thread.
+// Compare-exchange with lane ^ STRIDE: the lower lane of a pair keeps the larger key when desc.
+template <int STRIDE, typename T>
+__device__ __forceinline__ T cmpx_lane(T x, int lane, bool desc) {
+    T y;
+    if constexpr (sizeof(T) == 8) {
+        const uint32_t lo = xor_lane<STRIDE>((uint32_t)x, lane), hi = xor_lane<STRIDE>((uint32_t)(x >> 32), lane);
+        y = ((u64)hi << 32) | lo;
+    } else {
+        y = xor_lane<STRIDE>(x, lane);
     }
-    return *prefix_s;
+    return ((x > y) == (((lane & STRIDE) == 0) == desc)) ? x : y;
+}
+template <typename T>
+__device__ __forceinline__ T merge_in_wave(T x, int lane, bool desc) {
+    x = cmpx_lane<32>(x, lane, desc); x = cmpx_lane<16>(x, lane, desc); x = cmpx_lane<8>(x, lane, desc);
+    x = cmpx_lane<4>(x, lane, desc);  x = cmpx_lane<2>(x, lane, desc);  x = cmpx_lane<1>(x, lane, desc);
+    return x;
+}
+// Bitonic sort of the 64 keys of a wavefront, 21 register exchanges: lane 0 ends with the largest
+// when desc, with the smallest otherwise.
+template <typename T>
+__device__ __forceinline__ T sort_in_wave(T x, int lane, bool desc) {
+    x = cmpx_lane<1>(x, lane, (lane & 2) == 0);
+    x = cmpx_lane<2>(x, lane, (lane & 4) == 0);  x = cmpx_lane<1>(x, lane, (lane & 4) == 0);
+    x = cmpx_lane<4>(x, lane, (lane & 8) == 0);  x = cmpx_lane<2>(x, lane, (lane & 8) == 0);
+    x = cmpx_lane<1>(x, lane, (lane & 8) == 0);
+    x = cmpx_lane<8>(x, lane, (lane & 16) == 0); x = cmpx_lane<4>(x, lane, (lane & 16) == 0);
+    x = cmpx_lane<2>(x, lane, (lane & 16) == 0); x = cmpx_lane<1>(x, lane, (lane & 16) == 0);
+    x = cmpx_lane<16>(x, lane, (lane & 32) == 0); x = cmpx_lane<8>(x, lane, (lane & 32) == 0);
+    x = cmpx_lane<4>(x, lane, (lane & 32) == 0);  x = cmpx_lane<2>(x, lane, (lane & 32) == 0);
+    x = cmpx_lane<1>(x, lane, (lane & 32) == 0);
+    return merge_in_wave(x, lane, desc);
+}
+// Bitonic sort of the 1024 keys x, one per thread, over the workgroup: thread t returns the
+// (t+1)-th largest (equal keys in any order).  Steps between lanes of a wavefront are register
+// exchanges; the 10 steps between wavefronts go through buf (LDS, [2][1024], one barrier each).
+// (A radix select of the K-th largest alone was slower: its first histogram pass sends all 1024
+// atomic adds to the two or three bins of the common exponent, 3 us per pass.)
+template <typename T>
+__device__ __forceinline__ T wg_sort_desc_1024(T x, T* buf) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    x = sort_in_wave(x, lane, (tid & 64) == 0);
+    int pb = 0;
+#pragma unroll
+    for (int size = 128; size <= kKlThreads; size <<= 1) {
+        const bool desc = (tid & size) == 0;
+#pragma unroll
+        for (int stride = size >> 1; stride >= 64; stride >>= 1) {
+            buf[pb * kKlThreads + tid] = x;
+            __syncthreads();
+            const T y = buf[pb * kKlThreads + (tid ^ stride)];
+            pb ^= 1;                                     // the next step writes the other half
+            x = ((x > y) == (((tid & stride) == 0) == desc)) ? x : y;
+        }
+        x = merge_in_wave(x, lane, desc);
+    }
+    return x;
 }
 
+// The q-th largest (counting repeats, 1 <= q <= 64) of the 64 values of a wavefront: the largest t
+// that at least q values reach, found bit by bit.  One vector compare per bit, the rest is scalar:
+// with 8 wavefronts per SIMD this costs a fifth of sorting the 64 values.
+__device__ __forceinline__ uint32_t wave_kth_largest(uint32_t v, int q) {
+    uint32_t t = 0;
+#pragma unroll
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t c = t | (1u << bit);
+        if (__popcll(__ballot(v >= c)) >= q) t = c;              // (uniform)
+    }
+    return t;
+}
 // A lower bound of the K-th largest (counting repeats) of the 1024 values v, one per thread, without
-// a selection: every wavefront sorts its 64 values; with q = ceil(K / 16), each of the 16
-// wavefronts holds q values at or above its own q-th largest, so K values reach the smallest of the
-// 16.  (Looser than the exact K-th largest, which costs three radix passes with their barriers.)
-__device__ __forceinline__ u64 kth_bound_1024(u64 v, int K, u64* wave_q /*LDS [16]*/) {
+// a selection over the workgroup: with q = ceil(K / 16), each of the 16 wavefronts holds q values at or
+// above its own q-th largest, so K values reach the smallest of the 16.  (Looser than the exact K-th
+// largest, and a fraction of its cost.)
+__device__ __forceinline__ uint32_t kth_bound_1024(uint32_t v, int K, uint32_t* wave_q /*LDS [16]*/) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int q = (K + 15) >> 4;                               // K <= 1024
-    const u64 s = wave_sort_desc(v, lane);
-    if (lane == q - 1) wave_q[w] = s;
+    const uint32_t s = wave_kth_largest(v, q);
+    if (lane == 0) wave_q[w] = s;
     __syncthreads();
-    u64 t = wave_q[0];
+    uint32_t t = wave_q[0];
 #pragma unroll
-    for (int i = 1; i < kKlThreads / 64; ++i) { const u64 o = wave_q[i]; t = o < t ? o : t; }
+    for (int i = 1; i < kKlThreads / 64; ++i) { const uint32_t o = wave_q[i]; t = o < t ? o : t; }
     return t;
 }
 }  // namespace
@@ -122,14 +166,22 @@ __device__ __forceinline__ u64 kth_bound_1024(u64 v, int K, u64* wave_q /*LDS [1
 // Stage 1 of the selection, one workgroup per (slice g of the vocabulary, event e): the keys of the
 // slice that can still be among the event's K largest go to the workspace, unranked:
 // ws_keys[(e * G + g) * kKlCand + ...], their number to ws_cnt[e * G + g].
-__global__ void __launch_bounds__(kKlThreads)
+//
+// NL > 0: the slice fits NL 16-byte loads per thread (and the logits are 16-byte aligned).  All of
+// them are issued before the first is used and the values stay in registers for the second sweep:
+// the kernel is bound by memory latency, and a loop of dependent load-then-compare iterations pays
+// that latency once per iteration.  NL == 0: any size and alignment, two sweeps over memory.
+// (Two workgroups per compute unit, so that the 8 x E workgroups of 60 events run as one round: the
+// second launch-bounds figure caps the registers at 64 per lane; the radix path below may spill.)
+template <int NL>
+__global__ void __launch_bounds__(kKlThreads, 8)
 kl_select_slices_kernel(const float* __restrict__ z_target, int V, int K, int G, int slice,
                         u64* __restrict__ ws_keys, int* __restrict__ ws_cnt) {
     __shared__ __align__(16) uint32_t hist[kKlBins];
     __shared__ u64 cand[kKlCand];
     __shared__ int ncand;
     __shared__ u64 prefix_s;
-    __shared__ u64 wave_q[kKlThreads / 64];
+    __shared__ uint32_t wave_q[kKlThreads / 64];
     __shared__ int need_s, done_s;
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -143,32 +195,77 @@ kl_select_slices_kernel(const float* __restrict__ z_target, int V, int K, int G,
     if (tid == 0) { done_s = 0; ncand = 0; }
 
     // ---- common path: the Kl-th largest of the per-thread maxima bounds the slice's Kl-th largest
-    // logit from below (plain float compares; 16-byte loads when the logits are 16-byte aligned)
-    const bool vec = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(z_target) & 15) == 0;
+    // logit from below (plain float compares)
     float mx = -INFINITY;
     bool any = false;
-    if (vec) {
+    float4 q[NL > 0 ? NL : 1];
+    const bool vec = NL > 0 || ((V & 3) == 0 && (reinterpret_cast<uintptr_t>(z_target) & 15) == 0);
+    if constexpr (NL > 0) {
+        // (the launcher picks NL > 0 only for aligned logits and a slice that NL loads per thread cover)
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int i = lo + 4 * (tid + j * kKlThreads);
+            q[j] = *reinterpret_cast<const float4*>(z + (i < hi ? i : lo));     // past the end: a valid address, masked below
+        }
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const bool in = lo + 4 * (tid + j * kKlThreads) < hi;
+            if (!in) q[j] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            mx = fmaxf(fmaxf(mx, fmaxf(q[j].x, q[j].y)), fmaxf(q[j].z, q[j].w));
+            any = any || in;
+        }
+    } else if (vec) {
         for (int i = lo + 4 * tid; i < hi; i += 4 * kKlThreads) {
-            const float4 q = *reinterpret_cast<const float4*>(z + i);
-            mx = fmaxf(fmaxf(mx, fmaxf(q.x, q.y)), fmaxf(q.z, q.w));
+            const float4 v = *reinterpret_cast<const float4*>(z + i);
+            mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
             any = true;
         }
     } else {
         for (int i = lo + tid; i < hi; i += kKlThreads) { mx = fmaxf(mx, z[i]); any = true; }
     }
     // (absent threads contribute 0, below every real value)
-    const u64 kth = kth_bound_1024(any ? (u64)f32_to_ordered(mx) << 32 : 0ull, Kl, wave_q);
-    const float tau0 = kth ? ordered_to_f32((uint32_t)(kth >> 32)) : -INFINITY;   // too few threads saw a logit: keep all
+    const uint32_t kth = kth_bound_1024(any ? f32_to_ordered(mx) : 0u, Kl, wave_q);
+    const float tau0 = kth ? ordered_to_f32(kth) : -INFINITY;      // too few threads saw a logit: keep all
     auto consider = [&](float v, int i) {
         if (v >= tau0) {
             const int p = atomicAdd(&ncand, 1);
             if (p < kKlCand) cand[p] = make_key(v, i);
         }
     };
-    if (vec) {
+    if constexpr (NL > 0) {
+        // One atomic add per wavefront instead of one per key (they all go to the same counter):
+        // a lane's number of keys (<= 4 NL < 64) is summed over the lower lanes bit by bit.
+        const float* qf = reinterpret_cast<const float*>(q);
+        uint32_t pass = 0;                                       // (4 NL <= 32 bits) bit 4 j + c: component c of load j reaches the bound
+#pragma unroll
+        for (int x = 0; x < 4 * NL; ++x)
+            if (lo + 4 * (tid + (x >> 2) * kKlThreads) < hi && qf[x] >= tau0) pass |= 1u << x;
+        const int mine = __popc(pass);
+        int before = 0, total = 0;
+#pragma unroll
+        for (int bit = 0; bit < 6; ++bit) {
+            const u64 bal = __ballot((mine >> bit) & 1);
+            before += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u)) << bit;
+            total += __popcll(bal) << bit;
+        }
+        static_assert(4 * NL < 64, "a lane's count fits six bits");
+        int base = 0;
+        if (total > 0) {
+            if (lane == 0) base = atomicAdd(&ncand, total);
+            base = __builtin_amdgcn_readfirstlane(base);
+        }
+        int p = base + before;
+#pragma unroll
+        for (int x = 0; x < 4 * NL; ++x) {
+            if ((pass >> x) & 1u) {
+                if (p < kKlCand) cand[p] = make_key(qf[x], lo + 4 * (tid + (x >> 2) * kKlThreads) + (x & 3));
+                ++p;
+            }
+        }
+    } else if (vec) {
         for (int i = lo + 4 * tid; i < hi; i += 4 * kKlThreads) {
-            const float4 q = *reinterpret_cast<const float4*>(z + i);
-            consider(q.x, i); consider(q.y, i + 1); consider(q.z, i + 2); consider(q.w, i + 3);
+            const float4 v = *reinterpret_cast<const float4*>(z + i);
+            consider(v.x, i); consider(v.y, i + 1); consider(v.z, i + 2); consider(v.w, i + 3);
         }
     } else {
         for (int i = lo + tid; i < hi; i += kKlThreads) consider(z[i], i);
@@ -233,37 +330,99 @@ kl_select_slices_kernel(const float* __restrict__ z_target, int V, int K, int G,
 __global__ void __launch_bounds__(kKlThreads)
 kl_select_final_kernel(const u64* __restrict__ ws_keys, const int* __restrict__ ws_cnt, int G, int K,
                        int32_t* __restrict__ out_support, float* __restrict__ out_zt) {
-    __shared__ __align__(16) uint32_t hist[kKlBins];
-    __shared__ int need_s;
-    __shared__ u64 surv[16 * kKlMaxK];
+    __shared__ __align__(16) u64 surv[16 * kKlMaxK];
     __shared__ u64 sorted[kKlMaxK];
     __shared__ u64 tau_s;
     __shared__ int nsurv;
     const int tid = threadIdx.x, e = blockIdx.x;
     if (tid == 0) nsurv = 0;
+    // The slices' lists, taken as one sequence, are dealt out to the threads, wavefronts first
+    // (entry i to lane (i / 16) % 64 of wavefront i % 16, at most 16 per thread), so that every
+    // wavefront gets its share; all loads are requested before the first is used (counts, then
+    // keys) and the keys stay in registers.  0: no key.
+    constexpr int kMaxG = 8, kPer = kMaxG * kKlCand / kKlThreads;
+    int c[kMaxG + 1];                                            // c[g]: entries in the lists before g
+    c[0] = 0;
+#pragma unroll
+    for (int g = 0; g < kMaxG; ++g) c[g + 1] = g < G ? ws_cnt[e * G + g] : 0;
+#pragma unroll
+    for (int g = 0; g < kMaxG; ++g) c[g + 1] += c[g];
+    u64 key[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = (((tid & 63) << 4) | (tid >> 6)) + j * kKlThreads;
+        int g = 0, base = 0;
+#pragma unroll
+        for (int x = 1; x < kMaxG; ++x)
+            if (i >= c[x]) { g = x; base = c[x]; }
+        key[j] = i < c[kMaxG] ? ws_keys[((size_t)e * G + g) * kKlCand + (i - base)] : 0ull;
+    }
     u64 mx = 0;
-    for (int g = 0; g < G; ++g) {
-        const int n = ws_cnt[e * G + g];
-        const u64* lst = ws_keys + ((size_t)e * G + g) * kKlCand;
-        for (int i = tid; i < n; i += kKlThreads) { const u64 key = lst[i]; mx = key > mx ? key : mx; }
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) mx = key[j] > mx ? key[j] : mx;
+    // A bound that at least K keys reach: the K-th largest of the per-thread maxima.  First on the
+    // logits alone (32-bit sort, half the register exchanges): K threads hold a key at or above
+    // it.  With masses of equal logits more keys can reach it than the list holds; then on the whole
+    // 64-bit key: keys are distinct, so exactly K threads reach that bound and at most kPer K keys
+    // do.  (The cheap bound of the slices admits half as many keys again, and the ranking below
+    // grows with their square: measured slower.)
+    constexpr int kCap = kPer * kKlMaxK;
+    static_assert(kCap * 8 >= 2 * kKlThreads * 8, "the survivors' list doubles as the sort buffer");
+    {
+        const uint32_t srt = wg_sort_desc_1024((uint32_t)(mx >> 32), reinterpret_cast<uint32_t*>(surv));
+        if (tid == K - 1) tau_s = (u64)srt << 32;                // 0: fewer than K threads hold a key: keep all
     }
-    __syncthreads();
-    const u64 tau = kth_largest_1024(mx, K, 64, hist, &tau_s, &need_s);   // 0: fewer than K threads hold a key: keep all
-    for (int g = 0; g < G; ++g) {
-        const int n = ws_cnt[e * G + g];
-        const u64* lst = ws_keys + ((size_t)e * G + g) * kKlCand;
-        for (int i = tid; i < n; i += kKlThreads) {
-            const u64 key = lst[i];
-            if (key >= tau) { const int p = atomicAdd(&nsurv, 1); if (p < 16 * kKlMaxK) surv[p] = key; }
+    for (int attempt = 0;; ++attempt) {
+        __syncthreads();                                         // tau_s written, the sort buffer read
+        const u64 tau = tau_s;
+        __syncthreads();                                         // (tau_s is rewritten in the second attempt)
+        // (one atomic add per key: gathering them per wavefront first, as the slices do, costs more here)
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            if (key[j] != 0ull && key[j] >= tau) { const int p = atomicAdd(&nsurv, 1); if (p < kCap) surv[p] = key[j]; }
         }
+        __syncthreads();
+        if (nsurv <= kCap || attempt == 1) break;                // (uniform: every thread reads the same count)
+        __syncthreads();
+        if (tid == 0) nsurv = 0;
+        const u64 srt = wg_sort_desc_1024(mx, surv);
+        if (tid == K - 1) tau_s = srt;
     }
-    __syncthreads();
-    const int ns = nsurv < 16 * kKlMaxK ? nsurv : 16 * kKlMaxK;
-    for (int t = tid; t < ns; t += kKlThreads) {
-        const u64 mine = surv[t];
-        int r = 0;
-        for (int j = 0; j < ns; ++j) r += surv[j] > mine ? 1 : 0;
-        if (r < K) sorted[r] = mine;
+    // Rank by counting.  A group of P = 1, 2, 4 or 8 adjacent lanes takes two survivors (each key
+    // read from LDS serves two compares: the reads are what bounds this loop), every lane of the
+    // group its part of the list, 8 keys per step (the loop waits for LDS once per step).
+    const int ns = nsurv < kCap ? nsurv : kCap;
+    const int nh = (ns + 1) >> 1;
+    int P = 1;
+    while (P < 8 && nh * (2 * P) <= kKlThreads) P *= 2;
+    const int seg = ((ns + P - 1) / P + 7) & ~7;                 // keys per part, whole steps
+    const int lane = tid & 63;
+    for (int t0 = 0; t0 < nh * P; t0 += kKlThreads) {
+        const int idx = t0 + tid, i = idx / P, part = idx - i * P;
+        const bool live0 = i < nh, live1 = i + nh < ns;
+        const u64 mine0 = live0 ? surv[i] : ~0ull, mine1 = live1 ? surv[i + nh] : ~0ull;
+        const int j0 = part * seg, j1 = live0 ? (j0 + seg < ns ? j0 + seg : ns) : 0;
+        int r0 = 0, r1 = 0, j = j0;
+        for (; j + 8 <= j1; j += 8) {
+            ulonglong2 q[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const ulonglong2*>(surv + j + 2 * u);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                r0 += (q[u].x > mine0) + (q[u].y > mine0);
+                r1 += (q[u].x > mine1) + (q[u].y > mine1);
+            }
+        }
+        for (; j < j1; ++j) { const u64 o = surv[j]; r0 += o > mine0 ? 1 : 0; r1 += o > mine1 ? 1 : 0; }
+        // the P lanes of a group are adjacent and aligned: add their counts
+        uint32_t r = (uint32_t)r0 | ((uint32_t)r1 << 16);       // (both below 2^13)
+        if (P >= 2) r += xor_lane<1>(r, lane);
+        if (P >= 4) r += xor_lane<2>(r, lane);
+        if (P >= 8) r += xor_lane<4>(r, lane);
+        if (part == 0) {
+            if (live0 && (int)(r & 0xffffu) < K) sorted[r & 0xffffu] = mine0;
+            if (live1 && (int)(r >> 16) < K) sorted[r >> 16] = mine1;
+        }
     }
     __syncthreads();
     for (int r = tid; r < K; r += kKlThreads) {
@@ -354,8 +513,14 @@ hipError_t launch_kl_gate(const float* z_target, int E, int V, const void* h_dra
     const int slice = ((V + G - 1) / G + 3) / 4 * 4;
     u64* ws_keys = static_cast<u64*>(workspace);
     int* ws_cnt = reinterpret_cast<int*>(ws_keys + (size_t)E * G * kKlCand);
-    hipLaunchKernelGGL(kl_select_slices_kernel, dim3(G, E), dim3(kKlThreads), 0, stream, z_target, V, K, G, slice,
-                       ws_keys, ws_cnt);
+    // 16-byte loads per thread that cover a slice, when the logits allow them
+    const bool vec = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(z_target) & 15) == 0;
+    const int per_thread = (slice / 4 + kKlThreads - 1) / kKlThreads;
+    auto slices = kl_select_slices_kernel<0>;
+    if (vec && per_thread <= 2) slices = kl_select_slices_kernel<2>;
+    else if (vec && per_thread <= 5) slices = kl_select_slices_kernel<5>;
+    else if (vec && per_thread <= 8) slices = kl_select_slices_kernel<8>;
+    hipLaunchKernelGGL(slices, dim3(G, E), dim3(kKlThreads), 0, stream, z_target, V, K, G, slice, ws_keys, ws_cnt);
     hipLaunchKernelGGL(kl_select_final_kernel, dim3(E), dim3(kKlThreads), 0, stream, ws_keys, ws_cnt, G, K,
                        out_support, out_zt);
     hipLaunchKernelGGL(kl_draft_logits_kernel, dim3((K + 15) / 16, E), dim3(256), (size_t)d * 2, stream,

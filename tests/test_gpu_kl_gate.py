@@ -38,6 +38,8 @@ def check(got, want, where):
     (2, 70000, 264, 100, 2.0),      # ragged sizes, another temperature
     (4, 1000, 4096, 1, 1.0),        # K = 1: divergence is zero
     (2, 256, 128, 256, 0.5),        # K = V
+    (2, 30000, 64, 256, 1.0),       # one slice, eight 16-byte loads per thread
+    (2, 32770, 64, 256, 1.0),       # eight slices, rows not 16-byte aligned: the looping sweep
 ])
 def test_shapes(ev, E, V, d, K, T):
     from oracle import kl_gate
@@ -63,6 +65,28 @@ def test_ties_and_degenerate_logits(ev):
     got, want = run(ev, z, h, W, 256, 1.0), kl_gate(z, h, W, 256, 1.0)
     check(got, want, "ties")
     assert got[0][0].tolist() == list(range(256)) and got[0][1].tolist() == list(range(100, 356))
+
+
+def test_many_equal_logits_across_slices(ev):
+    """1,500 logits per eighth of the vocabulary tie at the top: every slice hands all of them on
+    (fewer than its list holds), 12,000 keys reach the bound on the logits alone, more than the
+    last stage's list holds, so it has to fall back to the bound on the whole (logit, id) key.
+    The support is then the 256 smallest ids among the tied ones."""
+    from oracle import kl_gate
+    V, d, E = 151936, 64, 2
+    rng = np.random.default_rng(77)
+    W = gi.gen_normal_bf16(V, d, 15, 0.05)
+    h = gi.gen_h(E, d, 16)
+    z = (rng.standard_normal((E, V)) * 0.5).astype(np.float32).clip(-4.0, 4.0)
+    tied = []
+    for e in range(E):
+        ids = np.concatenate([g * 18992 + rng.choice(18992, 1500, replace=False) for g in range(8)])
+        z[e, ids] = 5.0
+        tied.append(np.sort(ids))
+    got, want = run(ev, z, h, W, 256, 1.0), kl_gate(z, h, W, 256, 1.0)
+    check(got, want, "ties across slices")
+    for e in range(E):
+        assert got[0][e].tolist() == tied[e][:256].tolist()
 
 
 def test_full_size(ev):
