@@ -13,9 +13,10 @@
 //     64-bit (logit, id) keys.  If more than 2048 reach it (masses of equal logits), radix select on
 //     the key instead (11 bits per pass, histogram in LDS, a pass is skipped as soon as the bin that
 //     holds the K-th key is taken whole) leaves exactly K;
-//  2. kl_select_final_kernel, one workgroup per event: the exact K-th largest of the per-thread
-//     maxima of the slices' candidates (a bitonic sort over the workgroup) bounds the answer, the
-//     survivors (a few more than K) are ranked by counting: the support, by decreasing key;
+//  2. kl_select_final_kernel, one workgroup per event: the K-th largest of the maxima that pairs
+//     of threads hold of the slices' candidates (a bitonic sort over half the workgroup) bounds
+//     the answer, the survivors (a few more than K) are sorted the same way: the support, by
+//     decreasing key;
 //  3. kl_draft_logits_kernel, one workgroup of 4 wavefronts per 16 support rows of an event, so that
 //     the E x K rows of W_LM (the bulk of the bytes) are spread over the whole GPU: a wavefront
 //     takes 4 rows at a time, 16 bytes per lane and load, h in LDS;
@@ -108,28 +109,33 @@ __device__ __forceinline__ T sort_in_wave(T x, int lane, bool desc) {
     x = cmpx_lane<1>(x, lane, (lane & 32) == 0);
     return merge_in_wave(x, lane, desc);
 }
-// Bitonic sort of the 1024 keys x, one per thread, over the workgroup: thread t returns the
-// (t+1)-th largest (equal keys in any order).  Steps between lanes of a wavefront are register
-// exchanges; the 10 steps between wavefronts go through buf (LDS, [2][1024], one barrier each).
+// Bitonic sort of N keys (N = 512 or 1024), one per thread of the first N threads of the workgroup:
+// thread t < N returns the (t+1)-th largest (equal keys in any order); every thread of the workgroup
+// calls it (the others only meet the barriers).  Steps between lanes of a wavefront are register
+// exchanges; the steps between wavefronts go through buf (LDS, [2][N], one barrier each).
 // (A radix select of the K-th largest alone was slower: its first histogram pass sends all 1024
 // atomic adds to the two or three bins of the common exponent, 3 us per pass.)
-template <typename T>
-__device__ __forceinline__ T wg_sort_desc_1024(T x, T* buf) {
+template <int N, typename T>
+__device__ __forceinline__ T wg_sort_desc(T x, T* buf) {
+    static_assert(N % 128 == 0 && N <= kKlThreads, "whole wavefronts");
     const int tid = threadIdx.x, lane = tid & 63;
-    x = sort_in_wave(x, lane, (tid & 64) == 0);
+    const bool act = tid < N;                            // (uniform per wavefront)
+    if (act) x = sort_in_wave(x, lane, (tid & 64) == 0);
     int pb = 0;
 #pragma unroll
-    for (int size = 128; size <= kKlThreads; size <<= 1) {
+    for (int size = 128; size <= N; size <<= 1) {
         const bool desc = (tid & size) == 0;
 #pragma unroll
         for (int stride = size >> 1; stride >= 64; stride >>= 1) {
-            buf[pb * kKlThreads + tid] = x;
+            if (act) buf[pb * N + tid] = x;
             __syncthreads();
-            const T y = buf[pb * kKlThreads + (tid ^ stride)];
+            if (act) {
+                const T y = buf[pb * N + (tid ^ stride)];
+                x = ((x > y) == (((tid & stride) == 0) == desc)) ? x : y;
+            }
             pb ^= 1;                                     // the next step writes the other half
-            x = ((x > y) == (((tid & stride) == 0) == desc)) ? x : y;
         }
-        x = merge_in_wave(x, lane, desc);
+        if (act) x = merge_in_wave(x, lane, desc);
     }
     return x;
 }
@@ -360,17 +366,25 @@ kl_select_final_kernel(const u64* __restrict__ ws_keys, const int* __restrict__ 
     u64 mx = 0;
 #pragma unroll
     for (int j = 0; j < kPer; ++j) mx = key[j] > mx ? key[j] : mx;
-    // A bound that at least K keys reach: the K-th largest of the per-thread maxima.  First on the
-    // logits alone (32-bit sort, half the register exchanges): K threads hold a key at or above
-    // it.  With masses of equal logits more keys can reach it than the list holds; then on the whole
-    // 64-bit key: keys are distinct, so exactly K threads reach that bound and at most kPer K keys
-    // do.  (The cheap bound of the slices admits half as many keys again, and the ranking below
-    // grows with their square: measured slower.)
+    // A bound that at least K keys reach.  First the K-th largest of the 512 maxima of thread pairs
+    // (t, t + 512), on the logits alone: a 32-bit sort by half of the wavefronts; K pairs hold a key
+    // at or above it, and about 1.3 K keys reach it.  With masses of equal logits more keys can reach it than the list
+    // holds; then the K-th largest of the 1024 per-thread maxima on the whole 64-bit key: keys are
+    // distinct, so exactly K threads reach that bound and at most kPer K keys do.  (The cheap bound
+    // of the slices admits half as many keys again as the first one, and ranking them cost more
+    // than this sort: measured.)
     constexpr int kCap = kPer * kKlMaxK;
+    constexpr int kHalf = kKlThreads / 2;
     static_assert(kCap * 8 >= 2 * kKlThreads * 8, "the survivors' list doubles as the sort buffer");
+    static_assert(kKlMaxK <= kHalf, "the K-th largest of the pair maxima exists");
     {
-        const uint32_t srt = wg_sort_desc_1024((uint32_t)(mx >> 32), reinterpret_cast<uint32_t*>(surv));
-        if (tid == K - 1) tau_s = (u64)srt << 32;                // 0: fewer than K threads hold a key: keep all
+        uint32_t* b32 = reinterpret_cast<uint32_t*>(surv);
+        if (tid >= kHalf) b32[2 * kHalf + tid - kHalf] = (uint32_t)(mx >> 32);      // (behind the sort's two halves)
+        __syncthreads();
+        uint32_t pm = (uint32_t)(mx >> 32);
+        if (tid < kHalf) { const uint32_t o = b32[2 * kHalf + tid]; pm = o > pm ? o : pm; }
+        const uint32_t srt = wg_sort_desc<kHalf>(pm, b32);
+        if (tid == K - 1) tau_s = (u64)srt << 32;                // 0: fewer than K pairs hold a key: keep all
     }
     for (int attempt = 0;; ++attempt) {
         __syncthreads();                                         // tau_s written, the sort buffer read
@@ -385,43 +399,52 @@ kl_select_final_kernel(const u64* __restrict__ ws_keys, const int* __restrict__ 
         if (nsurv <= kCap || attempt == 1) break;                // (uniform: every thread reads the same count)
         __syncthreads();
         if (tid == 0) nsurv = 0;
-        const u64 srt = wg_sort_desc_1024(mx, surv);
+        const u64 srt = wg_sort_desc<kKlThreads>(mx, surv);
         if (tid == K - 1) tau_s = srt;
     }
-    // Rank by counting.  A group of P = 1, 2, 4 or 8 adjacent lanes takes two survivors (each key
-    // read from LDS serves two compares: the reads are what bounds this loop), every lane of the
-    // group its part of the list, 8 keys per step (the loop waits for LDS once per step).
     const int ns = nsurv < kCap ? nsurv : kCap;
-    const int nh = (ns + 1) >> 1;
-    int P = 1;
-    while (P < 8 && nh * (2 * P) <= kKlThreads) P *= 2;
-    const int seg = ((ns + P - 1) / P + 7) & ~7;                 // keys per part, whole steps
-    const int lane = tid & 63;
-    for (int t0 = 0; t0 < nh * P; t0 += kKlThreads) {
-        const int idx = t0 + tid, i = idx / P, part = idx - i * P;
-        const bool live0 = i < nh, live1 = i + nh < ns;
-        const u64 mine0 = live0 ? surv[i] : ~0ull, mine1 = live1 ? surv[i + nh] : ~0ull;
-        const int j0 = part * seg, j1 = live0 ? (j0 + seg < ns ? j0 + seg : ns) : 0;
-        int r0 = 0, r1 = 0, j = j0;
-        for (; j + 8 <= j1; j += 8) {
-            ulonglong2 q[4];
+    if (ns <= kHalf) {
+        // The usual case: the survivors fit one key per thread of half the workgroup, and sorting
+        // them there is cheaper than counting (every wavefront would read the whole list).
+        const u64 mine = tid < ns ? surv[tid] : 0ull;
+        __syncthreads();                                         // the list is in registers: its memory becomes the sort buffer
+        const u64 srt = wg_sort_desc<kHalf>(mine, surv);
+        if (tid < K) sorted[tid] = srt;                          // (ns >= K whenever K keys exist; K <= V is checked by the caller)
+    } else {
+        // Rank by counting.  A group of P = 1 or 2 adjacent lanes takes two survivors (each key
+        // read from LDS serves two compares: the reads are what bounds this loop), every lane of the
+        // group its part of the list, 8 keys per step (the loop waits for LDS once per step).
+        const int nh = (ns + 1) >> 1;
+        int P = 1;
+        while (P < 8 && nh * (2 * P) <= kKlThreads) P *= 2;
+        const int seg = ((ns + P - 1) / P + 7) & ~7;             // keys per part, whole steps
+        const int lane = tid & 63;
+        for (int t0 = 0; t0 < nh * P; t0 += kKlThreads) {
+            const int idx = t0 + tid, i = idx / P, part = idx - i * P;
+            const bool live0 = i < nh, live1 = i + nh < ns;
+            const u64 mine0 = live0 ? surv[i] : ~0ull, mine1 = live1 ? surv[i + nh] : ~0ull;
+            const int j0 = part * seg, j1 = live0 ? (j0 + seg < ns ? j0 + seg : ns) : 0;
+            int r0 = 0, r1 = 0, j = j0;
+            for (; j + 8 <= j1; j += 8) {
+                ulonglong2 q[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const ulonglong2*>(surv + j + 2 * u);
+                for (int u = 0; u < 4; ++u) q[u] = *reinterpret_cast<const ulonglong2*>(surv + j + 2 * u);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                r0 += (q[u].x > mine0) + (q[u].y > mine0);
-                r1 += (q[u].x > mine1) + (q[u].y > mine1);
+                for (int u = 0; u < 4; ++u) {
+                    r0 += (q[u].x > mine0) + (q[u].y > mine0);
+                    r1 += (q[u].x > mine1) + (q[u].y > mine1);
+                }
             }
-        }
-        for (; j < j1; ++j) { const u64 o = surv[j]; r0 += o > mine0 ? 1 : 0; r1 += o > mine1 ? 1 : 0; }
-        // the P lanes of a group are adjacent and aligned: add their counts
-        uint32_t r = (uint32_t)r0 | ((uint32_t)r1 << 16);       // (both below 2^13)
-        if (P >= 2) r += xor_lane<1>(r, lane);
-        if (P >= 4) r += xor_lane<2>(r, lane);
-        if (P >= 8) r += xor_lane<4>(r, lane);
-        if (part == 0) {
-            if (live0 && (int)(r & 0xffffu) < K) sorted[r & 0xffffu] = mine0;
-            if (live1 && (int)(r >> 16) < K) sorted[r >> 16] = mine1;
+            for (; j < j1; ++j) { const u64 o = surv[j]; r0 += o > mine0 ? 1 : 0; r1 += o > mine1 ? 1 : 0; }
+            // the P lanes of a group are adjacent and aligned: add their counts
+            uint32_t r = (uint32_t)r0 | ((uint32_t)r1 << 16);   // (both below 2^13)
+            if (P >= 2) r += xor_lane<1>(r, lane);
+            if (P >= 4) r += xor_lane<2>(r, lane);
+            if (P >= 8) r += xor_lane<4>(r, lane);
+            if (part == 0) {
+                if (live0 && (int)(r & 0xffffu) < K) sorted[r & 0xffffu] = mine0;
+                if (live1 && (int)(r >> 16) < K) sorted[r >> 16] = mine1;
+            }
         }
     }
     __syncthreads();
