@@ -102,8 +102,9 @@ int evospec_form_candidates(const int32_t *target_top, int n_target, const int32
  *   4. evospec_active_gather of the admitted (slot, id) pairs into W_act / act_ids.
  * h_target (bf16 [d]), W_lm (bf16 [V, d]), W_act (V_act rows in `layout`, see evospec.h), act_ids,
  * workspace are device pointers, 16-byte aligned; everything else is host memory.  The call WAITS for step 1 on `stream` (it needs the
- * ids on the host), uploads the admitted pairs with copies that are complete when they return (so the
- * next event may use any stream), and returns after the gather has been enqueued.  out_slots / out_ids
+ * ids on the host) and returns after the gather has been enqueued: up to 32 admitted pairs travel in
+ * the gather's kernel arguments, more are uploaded first with a copy that is complete when it returns
+ * (either way the next event may use any stream).  out_slots / out_ids
  * (host, max_insert entries each, may be NULL) receive the admitted pairs, *n_out their number.
  * workspace_bytes must be at least evospec_path_a_workspace_bytes(V, d, n_mips, max_insert).
  * All arguments, those of the final gather included (W_act, act_ids, layout, and V_act >= slot_base +

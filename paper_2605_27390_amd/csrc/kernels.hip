@@ -24,9 +24,7 @@ namespace evospec {
 // One workgroup per row.  Into a packed W_act the row's pieces go to their places in the operand
 // tiles (16-byte stores 256 bytes apart) and the pieces between d and the padded row length are
 // zeroed.
-__device__ __forceinline__ void gather_one_row(const GatherArgs& g, int i) {
-    const int32_t id = g.src_ids[i];
-    const int32_t s = g.slots ? g.slots[i] : i;
+__device__ __forceinline__ void gather_row(const GatherArgs& g, int32_t id, int32_t s) {
     if (id < 0 || id >= g.V || s < 0 || s >= g.V_act) return;      // uniform per workgroup
     const uint4* src = static_cast<const uint4*>(g.W_lm) + (size_t)id * g.row_vec;
     const int nt = blockDim.x;
@@ -65,11 +63,21 @@ __device__ __forceinline__ void gather_one_row(const GatherArgs& g, int i) {
     }
     if (threadIdx.x == 0) g.act_ids[s] = id;
 }
+__device__ __forceinline__ void gather_one_row(const GatherArgs& g, int i) {
+    gather_row(g, g.src_ids[i], g.slots ? g.slots[i] : i);
+}
 
 // grid-stride over the n rows of the update
 __global__ void __launch_bounds__(256)
 gather_rows_kernel(GatherArgs g) {
     for (int i = blockIdx.x; i < g.n; i += gridDim.x) gather_one_row(g, i);
+}
+
+// A small update whose (slot, id) pairs travel in the kernel arguments: a caller that has them on
+// the host (the failure event of Path A) needs no upload and no wait for one.
+__global__ void __launch_bounds__(256)
+gather_rows_inline_kernel(GatherArgs g, InlineRows r) {
+    gather_row(g, r.id[blockIdx.x], r.slot[blockIdx.x]);
 }
 
 // Rebuild of a row-major W_act (slot i = i): four rows per workgroup and round, so that every lane has
@@ -862,6 +870,17 @@ hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids,
     }
     const int grid = n < 8192 ? n : 8192;
     hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(256), 0, stream, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_inline(const void* W_lm, int V, int d, const int32_t* host_ids, const int32_t* host_slots,
+                                int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream, bool packed) {
+    if (n < 0 || n > kInlineRows) return hipErrorInvalidValue;
+    if (n == 0) return hipSuccess;
+    const GatherArgs g{W_lm, V, d / 8, nullptr, nullptr, n, W_act, act_ids, V_act, packed ? 1 : 0};
+    InlineRows r{};
+    for (int i = 0; i < n; ++i) { r.slot[i] = host_slots[i]; r.id[i] = host_ids[i]; }
+    hipLaunchKernelGGL(gather_rows_inline_kernel, dim3(n), dim3(256), 0, stream, g, r);
     return hipGetLastError();
 }
 

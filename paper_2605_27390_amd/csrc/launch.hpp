@@ -52,6 +52,10 @@ hipError_t launch_merge(const MergeSet& a, const MergeSet& b, int k, float* out_
 hipError_t launch_gather(const void* W_lm, int V, int d, const int32_t* src_ids, const int32_t* slots,
                          int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream,
                          bool packed = false);
+// The same for at most kInlineRows rows whose ids and slots are HOST arrays: they are passed to the
+// kernel by value, so the call neither uploads nor waits.
+hipError_t launch_gather_inline(const void* W_lm, int V, int d, const int32_t* host_ids, const int32_t* host_slots,
+                                int n, void* W_act, int32_t* act_ids, int V_act, hipStream_t stream, bool packed);
 // Retained-support KL gate (K <= 256, d * 2 bytes <= 48 KB of LDS); workspace of kl_gate_workspace_bytes.
 size_t kl_gate_workspace_bytes(int E, int V);
 hipError_t launch_kl_gate(const float* z_target, int E, int V, const void* h_draft, int d, const void* W_lm,

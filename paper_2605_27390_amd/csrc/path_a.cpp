@@ -8,6 +8,7 @@
 
 #include "evospec.h"
 #include "evospec_arc.h"
+#include "launch.hpp"
 
 namespace {
 constexpr size_t kAlign = 256;
@@ -87,10 +88,17 @@ int evospec_path_a_event(evospec_arc* arc, const void* h_target, int d, const vo
         if (out_ids) out_ids[i] = pairs[cap + i];
     }
     if (n_ins == 0) return EVOSPEC_OK;
-    // 4. the admitted rows into the compact matrix.  The two small uploads are complete when they
-    //    return (the host buffer is this call's own), whatever stream the next event uses.
-    if (hipMemcpyWithStream(upd, pairs.data(), (size_t)n_ins * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
-        hipMemcpyWithStream(upd + cap, pairs.data() + cap, (size_t)n_ins * 4, hipMemcpyHostToDevice, st) != hipSuccess)
+    // 4. the admitted rows into the compact matrix.  A usual event (at most kInlineRows rows) hands
+    //    its (slot, id) pairs to the kernel by value: no upload, nothing to wait for.  A larger one
+    //    uploads both lists at once (slots in the first cap entries, ids behind them, on the host as
+    //    on the device); the upload is complete when it returns (the host buffer is this call's own),
+    //    whatever stream the next event uses.
+    if (n_ins <= evospec::kInlineRows) {
+        const hipError_t e = evospec::launch_gather_inline(W_lm, V, d, pairs.data() + cap, pairs.data(), n_ins, W_act,
+                                                           act_ids, V_act, st, layout == EVOSPEC_PACKED);
+        return e == hipSuccess ? EVOSPEC_OK : evospec::record_hip_error(e);
+    }
+    if (hipMemcpyWithStream(upd, pairs.data(), (size_t)(cap + n_ins) * 4, hipMemcpyHostToDevice, st) != hipSuccess)
         return EVOSPEC_HIP_ERROR;
     return evospec_active_gather(W_lm, V, d, upd + cap, upd, n_ins, W_act, act_ids, V_act, layout, stream);
 }

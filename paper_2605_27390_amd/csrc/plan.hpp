@@ -83,6 +83,13 @@ struct GatherArgs {
     int packed = 0;
 };
 
+// Rows of a small update passed to the kernel by value (see launch_gather_inline).
+constexpr int kInlineRows = 32;
+struct InlineRows {
+    int32_t slot[kInlineRows];
+    int32_t id[kInlineRows];
+};
+
 struct Plan {
     int nw = 0, rgw = 0;     // wavefronts per workgroup, 16-row groups per wavefront
     int rc = 0;              // chunks in the W-operand ring

@@ -292,7 +292,8 @@ def test_arc_manager_drives_the_gather(ev, oracle_mod):
     assert len(arc.resident()) == cap
 
 
-def test_path_a_event_end_to_end(ev, oracle_mod):
+@pytest.mark.parametrize("max_insert", [32, 48])   # rows handed to the kernel by value / uploaded first
+def test_path_a_event_end_to_end(ev, oracle_mod, max_insert):
     """A failure event through the native entry point (exact inner-product search on the GPU,
     candidate formation, admission, gather) against the same steps done by the oracles."""
     import torch
@@ -301,15 +302,16 @@ def test_path_a_event_end_to_end(ev, oracle_mod):
     W = gi.gen_W_lm(V, d)
     core = gi.zipf_ranking(V, 31)[:n_core].astype(np.int32)
     row_ptr, col = gi.bigram_graph(V, 12)
-    params = dict(capacity=cap, p0=cap // 2, ghost_cap=cap, max_insert=32, min_residency=1, warmup_events=2,
+    params = dict(capacity=cap, p0=cap // 2, ghost_cap=cap, max_insert=max_insert, min_residency=1, warmup_events=2,
                   slot_base=n_core, core=core)
     arc, ref = ev.ArcManager(**params), ArcOracle(**params)
     Wd = to_dev_bf16(W)
     W_act = torch.zeros((n_core + cap, d), dtype=torch.bfloat16, device="cuda")
     act_ids = torch.full((n_core + cap,), -1, dtype=torch.int32, device="cuda")
     ev.active_gather(Wd, to_dev_i32(core), None, W_act, act_ids)
-    ws = torch.empty(ev.path_a_workspace_bytes(V, d, 10, 32), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ev.path_a_workspace_bytes(V, d, 10, max_insert), dtype=torch.uint8, device="cuda")
     rng = np.random.default_rng(8)
+    most = 0
     for e in range(12):
         h = gi.gen_h(1, d, 500 + e)
         target_top = rng.integers(0, V, 10).astype(np.int32)
@@ -327,8 +329,10 @@ def test_path_a_event_end_to_end(ev, oracle_mod):
         got = ev.path_a_event(arc, hd, Wd, target_top, 10, row_ptr, col, 8, W_act, act_ids, ws)
         want = ref.event(form_candidates(target_top, i[0].cpu().numpy(), row_ptr, col, 8))
         assert got == want, e
+        most = max(most, len(got))
         arc.advance(1); ref.advance(1)
     torch.cuda.synchronize()
+    assert most > 32 or max_insert <= 32                      # the larger limit is actually used
     res = ref.resident()
     n_act = n_core + len(res)
     active = np.concatenate([core, np.array([t for _, t in res], dtype=np.int32)])
